@@ -1,0 +1,113 @@
+"""fp64 oracle of the DiLoCo outer step with optional row-wise linear quantisation
+(test infrastructure only).
+
+Follows Sec. 4.1 eqs. 2-3 and Algorithm 1 (worker delta, average over K workers, SGD
+with Nesterov momentum) and Algorithm 2's "compress parameter delta" branch.  Readings:
+
+* theta^(t-1) in eq. 3 is the global copy before this outer step, the same tensor the
+  deltas were measured against.
+* The outer learning rate is folded into the momentum buffer exactly as printed:
+  u <- mu u + eta_out Psi ; theta <- theta - mu u - eta_out Psi.
+* The paper only says linear quantisation uses uniformly spaced levels; the workload
+  description fixes row-wise, absmax scale, round-to-nearest, 4 bit.  Because codes must
+  be reproducible bit for bit, this one stage is defined in IEEE fp32 arithmetic:
+      delta = fl32(theta_g) - fl32(theta_k)          (one fp32 subtraction)
+      amax  = max_j |delta_j| over the row, qmax = 2^(bits-1) - 1
+      scale = amax / qmax                            (fp32 division)
+      q_j   = clamp(rint(delta_j / scale), -qmax, qmax), ties to even; 0 if amax == 0
+      code  = q_j + 2^(bits-1); two 4-bit codes per byte, even column in the low nibble
+      dequantised value = float(q_j) * scale         (one fp32 multiplication)
+  One quantisation per worker, before the average.
+"""
+import numpy as np
+
+
+def pseudogradient(theta_g, theta_k):
+    """Delta_k = theta_global - theta_k  (Algorithm 1, parameter delta)."""
+    return np.asarray(theta_g, np.float64) - np.asarray(theta_k, np.float64)
+
+
+def average(deltas):
+    """Psi = (1/K) sum_k Delta_k  (eq. 2)."""
+    K = len(deltas)
+    acc = np.zeros_like(np.asarray(deltas[0], np.float64))
+    for d in deltas:
+        acc = acc + np.asarray(d, np.float64)
+    return acc / K
+
+
+def outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov=True):
+    """eq. 3.  nesterov=False is plain SGD with momentum: theta <- theta - u."""
+    theta_g = np.asarray(theta_g, np.float64)
+    u = mu * np.asarray(u_prev, np.float64) + eta_out * psi
+    if nesterov:
+        theta = theta_g - mu * u - eta_out * psi
+    else:
+        theta = theta_g - u
+    return theta, u
+
+
+def quantize_rowwise(theta_g_f32, theta_k_f32, bits=4):
+    """Row-wise linear quantisation of theta_g - theta_k, in fp32 as specified above.
+
+    Inputs are 2-D float32 arrays [rows, n] holding the stored values exactly.
+    Returns (q int8 [rows, n], scale float32 [rows])."""
+    tg = np.asarray(theta_g_f32, dtype=np.float32)
+    tk = np.asarray(theta_k_f32, dtype=np.float32)
+    assert tg.ndim == 2 and tg.shape == tk.shape
+    qmax = np.float32(2 ** (bits - 1) - 1)
+    delta = (tg - tk).astype(np.float32)
+    amax = np.max(np.abs(delta), axis=1).astype(np.float32)
+    scale = (amax / qmax).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    ratio = (delta / safe[:, None]).astype(np.float32)
+    q = np.clip(np.rint(ratio), -qmax, qmax)
+    q = np.where(scale[:, None] > 0, q, 0.0).astype(np.int8)
+    return q, scale
+
+
+def pack_codes4(q):
+    """Signed 4-bit levels [-7, 7] -> packed bytes: code = q + 8, even column low nibble."""
+    q = np.asarray(q, dtype=np.int16)
+    assert q.shape[-1] % 2 == 0
+    c = (q + 8).astype(np.uint8)
+    return (c[..., 0::2] | (c[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_codes4(packed):
+    p = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = (p & 0x0F).astype(np.int8) - 8
+    out[..., 1::2] = (p >> 4).astype(np.int8) - 8
+    return out
+
+
+def dequantize_rowwise(q, scale):
+    """float(q) * scale in fp32, returned as float32."""
+    return (np.asarray(q, np.float32) * np.asarray(scale, np.float32)[:, None]).astype(np.float32)
+
+
+def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0):
+    """One outer step on one 2-D tensor [rows, n].
+
+    theta_g, thetas[k]: stored values (float64 holding fp32/bf16-representable numbers).
+    Returns dict with theta (new global), u, psi, and for the quantised path the
+    per-worker levels q[k] and scales[k]."""
+    theta_g = np.asarray(theta_g, np.float64)
+    out = {}
+    deltas = []
+    if quant_bits:
+        out["q"], out["scales"] = [], []
+        for th in thetas:
+            q, s = quantize_rowwise(theta_g.astype(np.float32),
+                                    np.asarray(th, np.float64).astype(np.float32), quant_bits)
+            out["q"].append(q)
+            out["scales"].append(s)
+            deltas.append(dequantize_rowwise(q, s).astype(np.float64))
+    else:
+        for th in thetas:
+            deltas.append(pseudogradient(theta_g, th))
+    psi = average(deltas)
+    theta, u = outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov)
+    out.update(theta=theta, u=u, psi=psi)
+    return out

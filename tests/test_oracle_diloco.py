@@ -1,0 +1,161 @@
+"""Pins for oracle/diloco.py (CPU only): special cases fixed by the paper's equations,
+the library's SGD-with-Nesterov as the textbook form of eq. 3, and for the quantiser
+the half-step error bound, brute-force nearest-level search and hand-built rows."""
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+from oracle import diloco
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def test_zero_inner_steps_is_identity():
+    r = _rng(0)
+    tg = r.standard_normal((4, 6))
+    out = diloco.outer_step(tg, np.zeros_like(tg), [tg.copy(), tg.copy(), tg.copy()], eta_out=0.7, mu=0.9)
+    assert np.array_equal(out["psi"], np.zeros_like(tg))
+    assert np.array_equal(out["theta"], tg) and np.array_equal(out["u"], np.zeros_like(tg))
+
+
+def test_unit_lr_no_momentum_is_plain_averaging():
+    r = _rng(1)
+    tg = r.standard_normal((3, 8))
+    ths = [tg + 0.01 * r.standard_normal((3, 8)) for _ in range(5)]
+    out = diloco.outer_step(tg, r.standard_normal((3, 8)), ths, eta_out=1.0, mu=0.0)
+    assert np.max(np.abs(out["theta"] - np.mean(ths, axis=0))) < 1e-15
+
+
+def test_pseudogradient_sign_and_mean():
+    tg = np.array([[1.0, 2.0]])
+    ths = [np.array([[0.5, 2.5]]), np.array([[1.5, 0.5]])]
+    assert np.array_equal(diloco.pseudogradient(tg, ths[0]), np.array([[0.5, -0.5]]))
+    assert np.array_equal(diloco.average([diloco.pseudogradient(tg, t) for t in ths]),
+                          np.array([[0.0, 0.5]]))
+
+
+def test_matches_library_sgd_nesterov_over_several_outer_steps():
+    """Constant eta_out: eq. 3 equals torch.optim.SGD(nesterov) fed Psi as the gradient
+    (u = eta_out * buf).  mu = 0 is plain SGD; nesterov=False is heavy-ball."""
+    for (eta, mu, nesterov) in [(0.7, 0.9, True), (0.9, 0.8, True), (0.5, 0.0, True), (0.7, 0.9, False)]:
+        r = _rng(2)
+        th0 = r.standard_normal((4, 5))
+        p = torch.nn.Parameter(torch.from_numpy(th0.copy()))
+        opt = torch.optim.SGD([p], lr=eta, momentum=mu, nesterov=nesterov and mu > 0)
+        th, u = th0.copy(), np.zeros_like(th0)
+        for step in range(4):
+            K = 3
+            workers = [th - 0.05 * r.standard_normal(th.shape) for _ in range(K)]
+            out = diloco.outer_step(th, u, workers, eta_out=eta, mu=mu, nesterov=nesterov)
+            psi = np.mean([th - w for w in workers], axis=0)
+            p.grad = torch.from_numpy(psi.copy())
+            opt.step()
+            th, u = out["theta"], out["u"]
+            assert np.max(np.abs(th - p.detach().numpy())) < 1e-14
+            buf = opt.state[p].get("momentum_buffer")
+            if buf is not None:
+                assert np.max(np.abs(u - eta * buf.numpy())) < 1e-14
+
+
+def _f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def test_quantiser_error_bound_extremes_and_idempotence():
+    r = _rng(3)
+    rows, n = 64, 96
+    tg = _f32(r.standard_normal((rows, n)) * 0.02)
+    tk = _f32(tg - _f32(r.standard_normal((rows, n)) * 1e-2))
+    q, s = diloco.quantize_rowwise(tg, tk, 4)
+    assert q.dtype == np.int8 and q.min() >= -7 and q.max() <= 7
+    delta = (tg - tk).astype(np.float32)
+    deq = diloco.dequantize_rowwise(q, s)
+    ulp = np.spacing(np.abs(delta).astype(np.float32))
+    assert np.all(np.abs(deq.astype(np.float64) - delta) <= s[:, None].astype(np.float64) / 2 + ulp)
+    # the absmax element maps to +-7 and comes back as +-amax within an ulp
+    j = np.argmax(np.abs(delta), axis=1)
+    rr = np.arange(rows)
+    assert np.all(np.abs(q[rr, j]) == 7)
+    assert np.all(np.abs(deq[rr, j] - delta[rr, j]) <= 2 * np.spacing(np.abs(delta[rr, j])))
+    # quantising the dequantised values again reproduces codes and scales
+    q2, s2 = diloco.quantize_rowwise(deq, np.zeros_like(deq), 4)
+    assert np.array_equal(q2, q)
+    assert np.all(np.abs(s2 - s) <= np.spacing(s))
+
+
+def test_quantiser_brute_force_nearest_level():
+    """Independent definition: q is the level k in [-7,7] minimising |delta - k*scale|,
+    evaluated in exact rational arithmetic; the fp32 recipe may differ only when the
+    value sits within fp32 rounding of a midpoint."""
+    r = _rng(4)
+    rows, n = 16, 32
+    tg = _f32(r.standard_normal((rows, n)))
+    tk = _f32(r.standard_normal((rows, n)))
+    q, s = diloco.quantize_rowwise(tg, tk, 4)
+    delta = (tg - tk).astype(np.float32)
+    mism = 0
+    for i in range(rows):
+        sc = Fraction(float(s[i]))
+        for j in range(n):
+            d = Fraction(float(delta[i, j]))
+            best = min(range(-7, 8), key=lambda k: (abs(d - k * sc), abs(k)))
+            if best != int(q[i, j]):
+                frac = abs(abs(d / sc) - (abs(Fraction(best)) + abs(Fraction(int(q[i, j])))) / 2)
+                assert frac < Fraction(1, 2 ** 20), (i, j)
+                mism += 1
+    assert mism <= 2
+
+
+def test_quantiser_hand_rows_and_packing():
+    # amax = 7 -> scale exactly 1: levels are the integers, halves tie to even
+    tk = _f32([[0, 0, 0, 0, 0, 0, 0, 0], [0] * 8])
+    tg = _f32([[7.0, -7.0, 0.5, 1.5, 2.5, -0.5, -1.5, 3.49], [0] * 8])
+    q, s = diloco.quantize_rowwise(tg, tk, 4)
+    assert s[0] == np.float32(1.0) and s[1] == np.float32(0.0)
+    assert q[0].tolist() == [7, -7, 0, 2, 2, 0, -2, 3]
+    assert q[1].tolist() == [0] * 8
+    packed = diloco.pack_codes4(q)
+    assert packed.shape == (2, 4) and packed.dtype == np.uint8
+    # even column in the low nibble: (7+8) | ((-7+8) << 4) = 0x1F
+    assert packed[0, 0] == 0x1F and packed[0, 1] == ((2 + 8) << 4 | (0 + 8))
+    assert np.all(packed[1] == 0x88)
+    assert np.array_equal(diloco.unpack_codes4(packed), q)
+    deq = diloco.dequantize_rowwise(q, s)
+    assert deq[0].tolist() == [7, -7, 0, 2, 2, 0, -2, 3] and np.all(deq[1] == 0)
+
+
+def test_quantiser_enumerates_all_bf16_pairs_in_a_small_range():
+    """n = 2 rows over every pair of bf16 values with |x| in [2^-3, 2^-1): the larger
+    magnitude must code to +-7, the other to the nearest multiple of amax/7."""
+    mags = [(1 + m / 128.0) * 2.0 ** e for e in (-3, -2) for m in range(0, 128, 3)]
+    vals = np.array([v for m in mags for v in (m, -m)], dtype=np.float32)
+    a, b = np.meshgrid(vals, vals, indexing="ij")
+    tg = np.stack([a.ravel(), b.ravel()], axis=1)
+    q, s = diloco.quantize_rowwise(tg, np.zeros_like(tg), 4)
+    big = np.argmax(np.abs(tg), axis=1)
+    rr = np.arange(tg.shape[0])
+    assert np.all(q[rr, big] == 7 * np.sign(tg[rr, big]))
+    small = 1 - big
+    exact = tg[rr, small].astype(np.float64) * 7.0 / np.abs(tg[rr, big]).astype(np.float64)
+    assert np.all(np.abs(q[rr, small] - exact) <= 0.5 + 1e-6)
+
+
+def test_quantised_outer_step_uses_dequantised_deltas():
+    r = _rng(5)
+    tg = _f32(r.standard_normal((6, 16)) * 0.02).astype(np.float64)
+    ths = [(_f32(tg) - _f32(r.standard_normal((6, 16)) * 1e-2)).astype(np.float64) for _ in range(4)]
+    u0 = r.standard_normal((6, 16)) * 1e-3
+    out = diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8, quant_bits=4)
+    exact = diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8)
+    # psi differs from the exact mean by at most the mean half-step
+    half = np.mean([s for s in out["scales"]], axis=0)[:, None] / 2
+    assert np.all(np.abs(out["psi"] - exact["psi"]) <= half + 1e-9)
+    psi = np.mean([diloco.dequantize_rowwise(q, s).astype(np.float64)
+                   for q, s in zip(out["q"], out["scales"])], axis=0)
+    assert np.max(np.abs(psi - out["psi"])) < 1e-18
+    u = 0.8 * u0 + 0.9 * psi
+    assert np.max(np.abs(out["u"] - u)) < 1e-18
+    assert np.max(np.abs(out["theta"] - (tg - 0.8 * u - 0.9 * psi))) < 1e-17
