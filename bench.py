@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the MuLoCo optimizer hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over a synthetic transformer-shaped parameter
+set: a Muon inner step over every 2-D matrix of every resident worker replica (momentum +
+look-ahead + norm, batched Newton-Schulz, parameter update), one fused un-quantised outer
+step over all groups, and one 4-bit quantised outer step issued as a streaming schedule
+would issue it, one layer fragment per call.  All inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+The headline value is the Newton-Schulz matrix-core throughput: FLOP executed by the NS
+GEMM launches of the timed steps divided by the summed duration of those launches, each
+measured with HIP events on the stream the kernels run on (the library's timing recorder).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = ("Muon step ms + Newton–Schulz TFLOP/s (% MFMA peak); outer step GB/s (% HBM)")
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
+
+
+def cpu_baseline(workload, budget_s: float):
+    """Time the fp64 oracle (NumPy) on a bounded sample of the workload's matrices."""
+    import numpy as np
+    import synth_inputs as S
+    from oracle import muon
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    shapes = []
+    d, f = workload.d_model, workload.d_ffn
+    for (m, n) in [(d, d), (d, f)]:
+        shapes.append((min(m, 2048), min(n, 8192)))
+    flops = 0.0
+    t_used = 0.0
+    done = []
+    for (m, n) in shapes:
+        g = S.normal((m, n), S.GRAD_STD, 0, 999).numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        muon.newton_schulz(g, 5)
+        dt = time.perf_counter() - t0
+        s, l = min(m, n), max(m, n)
+        # the oracle always uses the m x m Gram form: 2 m^2 n + 2 m^3 + 2 m^2 n per iteration
+        flops += 5 * (4.0 * m * m * n + 2.0 * m ** 3)
+        t_used += dt
+        done.append(f"{m}x{n}")
+        if t_used > budget_s:
+            break
+    return {"value": flops / t_used * 1e-12, "unit": "TFLOP/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": "fp64 NumPy Newton-Schulz (5 iterations) on one matrix each of " + ", ".join(done),
+            "seconds": round(t_used, 2)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="1.76b", help="tiny | 150m | 1.76b | 3.1b | 15b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--workspace-gb", type=float, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    import synth_inputs as S
+    import paper_2505_23725_amd as mlc
+    from paper_2505_23725_amd.harness import MulocoJob
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    mlc.library()   # raises if the HIP library is not built
+    wl = S.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    cap = None if args.workspace_gb is None else int(args.workspace_gb * 2 ** 30)
+    if cap is None and args.workload in ("15b", "3.1b"):
+        cap = 8 * 2 ** 30
+    job = MulocoJob(wl, device="cuda:0", seed=0, with_quant=True, generate_on="device",
+                    workspace_cap_bytes=cap)
+    job.draw_gradients(0)
+    n_layers = wl.layers
+
+    def step():
+        job.inner_step()                       # a1-a6, batched per shape group (a11)
+        job.outer_step(0)                      # a7
+        hp = job.outer_hparams(quant_bits=4)
+        for layer in range(n_layers):          # a8 + a9 as a10: one layer fragment per call
+            mlc.muloco_outer_step(job.layer_fragment(layer, quant=True), hp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    mlc.muloco_timing_enable(True)
+    mlc.muloco_timing_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    timing = mlc.muloco_timing_read()
+    mlc.muloco_timing_enable(False)
+
+    ms_per_step = wall * 1e3 / args.steps
+    gemm = timing["ns_gemm"]
+    ns_tflops = gemm["flops"] / (gemm["total_ms"] * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
+
+    def fam(name):
+        t = timing[name]
+        gbs = t["bytes"] / (t["total_ms"] * 1e-3) * 1e-9 if t["total_ms"] > 0 else 0.0
+        return {"ms_per_step": t["total_ms"] / args.steps, "launches_per_step": t["launches"] / args.steps,
+                "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+
+    inner_ms = sum(timing[k]["total_ms"] for k in ("ns_gemm", "momentum", "norm", "update")) / args.steps
+    breakdown = {
+        "muon_inner_step_ms": inner_ms,
+        "ns_gemm_ms_per_step": gemm["total_ms"] / args.steps,
+        "ns_gemm_launches_per_step": gemm["launches"] / args.steps,
+        "ns_flop_per_step": gemm["flops"] / args.steps,
+        "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
+        "quantize": fam("quantize"), "dequant_outer": fam("dequant_outer"),
+    }
+    out = {
+        "metric": METRIC,
+        "value": ns_tflops,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}-scale: {wl.layers} layers, d_model {wl.d_model}, FFN {wl.d_ffn}, "
+                               f"K={job.K} replicas, {wl.param_dtype} params, fp32 momentum",
+                   "params_2d": wl.n_params(), "ns_iters": 5,
+                   "step": "muon inner step + fused outer step + 4-bit quantised outer step per layer fragment"},
+        "roofline": {"bound": "mfma", "achieved": ns_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ns_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "ns_gemm_bf16_kernel",
+                     "avg_launch_ms": gemm["total_ms"] / max(1, gemm["launches"])},
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_budget)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,208 @@
+/*
+ * muloco.h -- C ABI of the MI355X (gfx950) MuLoCo optimizer hot path.
+ *
+ * Three operations, named after the method they implement:
+ *   newton_schulz       quintic Newton-Schulz orthogonalisation of a batch of matrices
+ *   muloco_inner_step   one Muon step (momentum, look-ahead, orthogonalisation, update)
+ *   muloco_outer_step   one DiLoCo outer step over K resident worker replicas
+ * plus muloco_quantize_delta, the compressor of the outer step as a call of its own.
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller and 16-byte aligned.
+ *     Arrays of structs and arrays of pointers (groups, worker lists) are HOST memory and
+ *     are only read during the call.
+ *   - A "group" is `count` row-major matrices of one shape, contiguous: [count][m][n].
+ *   - bf16 buffers hold IEEE bfloat16 bit patterns (uint16_t); conversions from fp32
+ *     round to nearest, ties to even.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue kernels on it; they never allocate, free or synchronise.  Work spaces are
+ *     passed in by the caller and may be reused by the next call on the same stream.
+ *   - Return value: MLC_OK or a negative MLC_ERR_* code.  Arguments are validated on the
+ *     host before anything is enqueued; on an argument error no buffer is touched.
+ *   - The library keeps no mutable state apart from the optional timing recorder.
+ *   - Buffers must not overlap unless a parameter is documented as in/out or aliasable.
+ */
+#ifndef MULOCO_H_
+#define MULOCO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MLC_F32 = 0, MLC_BF16 = 1 } mlc_dtype;
+
+enum {
+  MLC_OK = 0,
+  MLC_ERR_NULL = -1,        /* a required pointer is NULL */
+  MLC_ERR_SHAPE = -2,       /* count/m/n < 1, overflow, odd row length for 4-bit codes */
+  MLC_ERR_DTYPE = -3,       /* not an mlc_dtype */
+  MLC_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or too small */
+  MLC_ERR_ARG = -5,         /* scalar argument out of range (iters < 0, K < 1, ...) */
+  MLC_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch */
+  MLC_ERR_UNSUPPORTED = -7  /* valid request this build does not implement */
+};
+
+#define MLC_MAX_WORKERS 32  /* largest K accepted by the outer step */
+
+/* Human-readable name of a return code (static string, never NULL). */
+const char* muloco_strerror(int code);
+
+/* ------------------------------------------------------------------------------------
+ * Newton-Schulz orthogonalisation (paper Sec. 2, paragraph "Muon").
+ *
+ * For each of the `count` matrices U (m x n):
+ *     X_0 = U / (||U||_F + eps)
+ *     X_j = a X_{j-1} + b (X X^T) X_{j-1} + c (X X^T)^2 X_{j-1},   j = 1..iters
+ *     out = X_iters
+ * i.e. the odd quintic p(s) = a s + b s^3 + c s^5 applied to the singular values,
+ * approximating the polar factor U V^T.  The paper uses (a, b, c) = (3.4445, -4.7750,
+ * 2.0315) and iters = 5.  The products run on the bf16 matrix cores with fp32
+ * accumulation; X, X X^T and the polynomial are held in bf16 between products, so the
+ * result carries about 1e-2 relative Frobenius error with respect to exact arithmetic.
+ * Tall matrices (m > n) use the algebraically identical n x n form with X^T X.
+ *
+ * in, out     [count][m][n] of `io` dtype; `out` may alias `in`.
+ * iters       >= 0; 0 returns the normalised input.
+ * workspace   at least newton_schulz_workspace_bytes(count, m, n) bytes, 256-byte
+ *             aligned.  A smaller work space that still holds one matrix is accepted;
+ *             the batch is then processed in several chunks.
+ * An all-zero matrix gives an all-zero result.
+ */
+size_t newton_schulz_workspace_bytes(int64_t count, int64_t m, int64_t n);
+/* Smallest accepted work space (one matrix per chunk). */
+size_t newton_schulz_workspace_min_bytes(int64_t m, int64_t n);
+int newton_schulz(const void* in, void* out, int io_dtype,
+                  int64_t count, int64_t m, int64_t n,
+                  int iters, float a, float b, float c, float eps,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Muon inner step (paper Sec. 2 "Muon"; Sec. 4.1 eq. 1; Algorithm 1, the Muon line;
+ * Sec. 5 "MuLoCo" for the per-shape learning-rate rescale).
+ *
+ * Per matrix W with gradient g and momentum accumulator mom:
+ *     mom <- beta * mom + g
+ *     U    = g + beta * mom            if nesterov, else U = mom
+ *     O    = newton_schulz(U)          (as above)
+ *     W   <- W - eta * lr_scale * O - eta * weight_decay * W
+ * The paper asks for lr_scale = sqrt(n/m) for an m x n matrix; the caller supplies it.
+ */
+typedef struct {
+  int64_t count, m, n;
+  void* param;           /* W, in/out, [count][m][n] of param_dtype                    */
+  int param_dtype;       /* mlc_dtype                                                  */
+  const void* grad;      /* g, in, same shape, grad_dtype                              */
+  int grad_dtype;        /* mlc_dtype                                                  */
+  float* momentum;       /* mom, fp32, in/out, same shape                              */
+  float lr_scale;        /* multiplies eta on the orthogonalised term only             */
+} mlc_inner_group;
+
+typedef struct {
+  float eta;             /* inner learning rate                                        */
+  float weight_decay;    /* lambda, decoupled: the decay term is eta * lambda * W      */
+  float beta;            /* momentum coefficient                                       */
+  int nesterov;          /* 1: U = g + beta * mom_t ; 0: U = mom_t                     */
+  int ns_iters;          /* Newton-Schulz iterations (paper: 5)                        */
+  float ns_a, ns_b, ns_c;/* polynomial coefficients (paper: 3.4445, -4.7750, 2.0315)   */
+  float ns_eps;          /* added to the Frobenius norm (1e-7)                         */
+} mlc_muon_hparams;
+
+/* Work space that lets every group run as a single batch (the largest group decides). */
+size_t muloco_inner_workspace_bytes(const mlc_inner_group* groups, int n_groups);
+/* Smallest accepted work space (every group processed one matrix at a time). */
+size_t muloco_inner_workspace_min_bytes(const mlc_inner_group* groups, int n_groups);
+/* groups: host array.  Same-shape matrices of a group are batched into each launch. */
+int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
+                      const mlc_muon_hparams* hp,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * DiLoCo outer step (paper Sec. 4.1 eqs. 2-3; Algorithm 1, the four lines after the
+ * inner loop; Algorithm 2, "compress parameter delta", for the quantised path).
+ *
+ * Per element, with K worker replicas resident on this GPU:
+ *     Delta_k = theta_g - theta_k
+ *     Delta_k = dequantise(quantise(Delta_k))        only if quant_bits != 0
+ *     Psi     = (1/K) sum_k Delta_k
+ *     u      <- mu * u + eta_out * Psi
+ *     theta_g<- theta_g - mu * u - eta_out * Psi     (nesterov = 1)
+ *     theta_g<- theta_g - u                          (nesterov = 0)
+ *     theta_k<- theta_g for every k                  (write_back = 1)
+ *
+ * Quantiser (quant_bits = 4): row-wise linear, symmetric, defined in IEEE fp32 so that
+ * codes are reproducible bit for bit.  For each row (length n) of each matrix:
+ *     delta = fl32(theta_g) - fl32(theta_k);  amax = max |delta|;  scale = amax / 7
+ *     q = clamp(rint(delta / scale), -7, 7) (ties to even), q = 0 when amax = 0
+ *     code = q + 8 in [1, 15]; byte i of a row = code[2i] | code[2i+1] << 4
+ *     dequantised value = (float)q * scale
+ * A "fragment" for streaming synchronisation is simply a call with a subset of groups.
+ */
+typedef struct {
+  int64_t count, m, n;           /* rows for the quantiser: count * m rows of length n */
+  void* const* worker_params;    /* HOST array of K device pointers theta_k; read, and
+                                    written when write_back = 1                        */
+  int worker_dtype;              /* mlc_dtype                                          */
+  void* global_param;            /* theta_g, in/out                                    */
+  int global_dtype;              /* mlc_dtype                                          */
+  float* outer_momentum;         /* u, fp32, in/out                                    */
+  uint8_t* const* codes;         /* HOST array of K device pointers, each
+                                    [count*m][n/2] packed codes; needed iff quant_bits */
+  float* const* scales;          /* HOST array of K device pointers, each [count*m]    */
+} mlc_outer_group;
+
+typedef struct {
+  int K;                 /* number of worker replicas, 1..MLC_MAX_WORKERS              */
+  float eta_out;         /* outer learning rate                                        */
+  float mu;              /* outer momentum                                             */
+  int nesterov;          /* 1: eq. 3 as printed ; 0: theta_g <- theta_g - u            */
+  int quant_bits;        /* 0: exchange fp32 deltas ; 4: row-wise 4-bit codes          */
+  int write_back;        /* 1: copy the new theta_g into every worker replica          */
+} mlc_outer_hparams;
+
+/* Needs no work space.  With quant_bits = 4 it first writes codes/scales (exactly what
+ * muloco_quantize_delta writes) and then consumes them. */
+int muloco_outer_step(const mlc_outer_group* groups, int n_groups,
+                      const mlc_outer_hparams* hp, void* stream);
+
+/* Only the compressor: fills codes[k] and scales[k] for every worker; nothing else is
+ * written.  hp->quant_bits must be 4. */
+int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups,
+                          const mlc_outer_hparams* hp, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Optional timing recorder (for benchmarks; not part of the method).
+ *
+ * While enabled, every kernel launch of this library is bracketed by HIP events on the
+ * stream it is launched on.  muloco_timing_read waits for the recorded events, adds
+ * each launch's duration to its kernel family and clears the record.  Enabling creates
+ * HIP events (host-side objects); it never allocates device memory.
+ */
+enum {
+  MLC_KERNEL_NS_GEMM = 0,     /* batched bf16 MFMA product of Newton-Schulz            */
+  MLC_KERNEL_MOMENTUM = 1,    /* momentum + look-ahead + sum of squares                */
+  MLC_KERNEL_NORM = 2,        /* per-matrix 1 / (norm + eps)                           */
+  MLC_KERNEL_UPDATE = 3,      /* parameter update                                      */
+  MLC_KERNEL_OUTER = 4,       /* fused pseudogradient / average / outer update         */
+  MLC_KERNEL_QUANTIZE = 5,    /* row-wise 4-bit quantiser                              */
+  MLC_KERNEL_DEQUANT_OUTER = 6,/* dequantise + average + outer update                  */
+  MLC_KERNEL_CONVERT = 7,     /* layout / dtype conversion around newton_schulz        */
+  MLC_KERNEL_FAMILIES = 8
+};
+typedef struct {
+  int64_t launches;      /* launches recorded since the last read                      */
+  double total_ms;       /* sum of their durations                                     */
+  double flops;          /* matrix-core FLOP executed by those launches (0 if n/a)     */
+  double bytes;          /* algorithmic HBM bytes of those launches (0 if n/a)         */
+} mlc_kernel_timing;
+
+int muloco_timing_enable(int on);
+/* out: HOST array of MLC_KERNEL_FAMILIES entries.  Synchronises with recorded events. */
+int muloco_timing_read(mlc_kernel_timing* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MULOCO_H_ */

@@ -1,0 +1,438 @@
+// C-ABI entry points, host-side argument validation, launch planning and the optional
+// timing recorder.  Nothing here allocates device memory or synchronises the stream.
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace mlc {
+
+// ---- timing recorder -------------------------------------------------------------
+namespace {
+struct TimingRecord { int family; hipEvent_t start, stop; double flops, bytes; };
+struct TimingState {
+  std::mutex mu;
+  bool enabled = false;
+  std::vector<TimingRecord> records;
+  std::vector<hipEvent_t> pool;
+};
+TimingState& timing() { static TimingState s; return s; }
+constexpr size_t kMaxRecords = 1u << 18;
+
+hipEvent_t get_event(TimingState& t) {
+  if (!t.pool.empty()) { hipEvent_t e = t.pool.back(); t.pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+}  // namespace
+
+LaunchScope::LaunchScope(int family, hipStream_t s, double flops, double bytes) : slot(-1), stream(s) {
+  TimingState& t = timing();
+  if (!t.enabled) return;
+  std::lock_guard<std::mutex> lock(t.mu);
+  if (t.records.size() >= kMaxRecords) return;
+  TimingRecord r{family, get_event(t), get_event(t), flops, bytes};
+  if (!r.start || !r.stop) return;
+  (void)hipEventRecord(r.start, stream);
+  t.records.push_back(r);
+  slot = (int)t.records.size() - 1;
+}
+LaunchScope::~LaunchScope() {
+  if (slot < 0) return;
+  TimingState& t = timing();
+  std::lock_guard<std::mutex> lock(t.mu);
+  if (slot < (int)t.records.size()) (void)hipEventRecord(t.records[slot].stop, stream);
+}
+
+namespace {
+
+constexpr int64_t PAD = 128;               // GEMM tile granularity of the work-space layout
+constexpr int64_t WS_ALIGN = 256;
+constexpr int MAX_NBLK = 1024;             // workgroups per matrix in the norm reduction
+constexpr int64_t MAX_CHUNK = 65535;       // gridDim.y limit
+
+bool valid_dtype(int d) { return d == MLC_F32 || d == MLC_BF16; }
+
+int check_shape(int64_t count, int64_t m, int64_t n) {
+  if (count < 1 || m < 1 || n < 1) return MLC_ERR_SHAPE;
+  const int64_t lim = (int64_t)1 << 30;    // per-dimension limit keeps int indexing valid
+  if (m > lim || n > lim || count > lim) return MLC_ERR_SHAPE;
+  const int64_t mp = round_up(m, PAD), np = round_up(n, PAD);
+  if (mp > ((int64_t)1 << 31) / np) {      // one padded matrix must stay below 2^31 elements
+    return MLC_ERR_SHAPE;
+  }
+  if ((double)count * (double)mp * (double)np >= 4.0e18) return MLC_ERR_SHAPE;
+  return MLC_OK;
+}
+
+// Work-space layout for a chunk of c matrices:  X0 | X1 | A | B | scale | partials
+struct NsPlan {
+  int64_t m, n, mp, np, sp;
+  int nblk;
+  size_t per_matrix;       // bytes that scale with the chunk size
+  size_t x_bytes, s_bytes; // per matrix
+};
+
+NsPlan make_plan(int64_t m, int64_t n) {
+  NsPlan p;
+  p.m = m; p.n = n;
+  p.mp = round_up(m, PAD); p.np = round_up(n, PAD);
+  p.sp = p.mp < p.np ? p.mp : p.np;
+  const int64_t items = p.mp * (p.np / 8);
+  int64_t nblk = items / (256 * 4);
+  if (nblk < 1) nblk = 1;
+  if (nblk > MAX_NBLK) nblk = MAX_NBLK;
+  p.nblk = (int)nblk;
+  p.x_bytes = (size_t)p.mp * p.np * 2;
+  p.s_bytes = (size_t)p.sp * p.sp * 2;
+  p.per_matrix = 2 * p.x_bytes + 2 * p.s_bytes + (size_t)WS_ALIGN /*scale slot*/ +
+                 (size_t)round_up((int64_t)p.nblk * 4, WS_ALIGN);
+  return p;
+}
+
+struct NsBuffers { bf16_t* X[2]; bf16_t* A; bf16_t* B; float* scale; float* partials; };
+
+NsBuffers carve(const NsPlan& p, void* ws, int64_t chunk) {
+  unsigned char* base = (unsigned char*)ws;
+  NsBuffers b;
+  b.X[0] = (bf16_t*)base; base += p.x_bytes * chunk;
+  b.X[1] = (bf16_t*)base; base += p.x_bytes * chunk;
+  b.A = (bf16_t*)base; base += p.s_bytes * chunk;
+  b.B = (bf16_t*)base; base += p.s_bytes * chunk;
+  b.scale = (float*)base; base += (size_t)WS_ALIGN * chunk;
+  b.partials = (float*)base;
+  return b;
+}
+
+int64_t chunk_for(const NsPlan& p, size_t ws_bytes, int64_t count) {
+  int64_t c = (int64_t)(ws_bytes / p.per_matrix);
+  if (c > count) c = count;
+  if (c > MAX_CHUNK) c = MAX_CHUNK;
+  return c;
+}
+
+// The `iters` Newton-Schulz iterations on a chunk whose (unnormalised) input sits in X[0]
+// and whose per-matrix 1/(norm+eps) sits in `scale`.  Returns the index of the buffer that
+// holds the result; with iters == 0 the result is X[0] still unscaled.
+//
+// The polynomial is folded before the last product: B' = a I + b A + c A^2, X <- B' X,
+// which is the printed iteration with one rounding to bf16 fewer.  The normalisation is
+// folded into the first iteration's scalars: A_0 = s^2 U U^T, X_1 = s B' U.
+int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
+                 float c, hipStream_t stream, int* result_buf) {
+  const bool wide = p.mp <= p.np;
+  const int64_t xs = p.mp * p.np, ss = p.sp * p.sp;
+  int cur = 0;
+  for (int it = 0; it < iters; ++it) {
+    const bf16_t* X = w.X[cur];
+    bf16_t* Xn = w.X[cur ^ 1];
+    GemmDesc g{};
+    // Gram matrix: A = X X^T (wide) or X^T X (tall)
+    g.A = X; g.lda = p.np; g.strideA = xs; g.a_kstrided = wide ? 0 : 1;
+    g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = wide ? 0 : 1;
+    g.D = w.A; g.ldd = p.sp; g.strideD = ss;
+    g.C = nullptr;
+    g.M = (int)p.sp; g.N = (int)p.sp; g.K = (int)(wide ? p.np : p.mp); g.batch = (int)chunk;
+    g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
+    g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 2;
+    int rc = launch_ns_gemm(g, stream);
+    if (rc != MLC_OK) return rc;
+    // Polynomial: B' = c A A + b A + a I   (A symmetric, so A A^T = A A)
+    g = GemmDesc{};
+    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
+    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
+    g.D = w.B; g.ldd = p.sp; g.strideD = ss;
+    g.C = w.A; g.ldc = p.sp; g.strideC = ss;
+    g.M = g.N = g.K = (int)p.sp; g.batch = (int)chunk;
+    g.alpha = c; g.beta = b; g.gamma = a;
+    rc = launch_ns_gemm(g, stream);
+    if (rc != MLC_OK) return rc;
+    // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
+    g = GemmDesc{};
+    if (wide) {
+      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
+      g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = 1;
+      g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
+    } else {
+      g.A = X; g.lda = p.np; g.strideA = xs; g.a_kstrided = 0;
+      g.B = w.B; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
+      g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.np;
+    }
+    g.D = Xn; g.ldd = p.np; g.strideD = xs;
+    g.C = nullptr; g.batch = (int)chunk;
+    g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
+    g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 1;
+    rc = launch_ns_gemm(g, stream);
+    if (rc != MLC_OK) return rc;
+    cur ^= 1;
+  }
+  *result_buf = cur;
+  return MLC_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, size_t need) {
+  if (!ws) return MLC_ERR_WORKSPACE;
+  if (((uintptr_t)ws) % WS_ALIGN) return MLC_ERR_WORKSPACE;
+  if (bytes < need) return MLC_ERR_WORKSPACE;
+  return MLC_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p) % 16 == 0; }
+
+size_t elem_size(int dtype) { return dtype == MLC_F32 ? 4 : 2; }
+
+}  // namespace
+}  // namespace mlc
+
+using namespace mlc;
+
+extern "C" {
+
+const char* muloco_strerror(int code) {
+  switch (code) {
+    case MLC_OK: return "ok";
+    case MLC_ERR_NULL: return "null pointer";
+    case MLC_ERR_SHAPE: return "bad shape";
+    case MLC_ERR_DTYPE: return "bad dtype";
+    case MLC_ERR_WORKSPACE: return "workspace null, misaligned or too small";
+    case MLC_ERR_ARG: return "argument out of range";
+    case MLC_ERR_LAUNCH: return "kernel launch failed";
+    case MLC_ERR_UNSUPPORTED: return "unsupported combination";
+    default: return "unknown error";
+  }
+}
+
+size_t newton_schulz_workspace_min_bytes(int64_t m, int64_t n) {
+  if (check_shape(1, m, n) != MLC_OK) return 0;
+  return make_plan(m, n).per_matrix;
+}
+
+size_t newton_schulz_workspace_bytes(int64_t count, int64_t m, int64_t n) {
+  if (check_shape(count, m, n) != MLC_OK) return 0;
+  const int64_t c = count > MAX_CHUNK ? MAX_CHUNK : count;
+  return make_plan(m, n).per_matrix * (size_t)c;
+}
+
+int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_t m, int64_t n,
+                  int iters, float a, float b, float c, float eps, void* workspace,
+                  size_t workspace_bytes, void* stream_) {
+  if (!in || !out) return MLC_ERR_NULL;
+  if (!valid_dtype(io_dtype)) return MLC_ERR_DTYPE;
+  int rc = check_shape(count, m, n);
+  if (rc != MLC_OK) return rc;
+  if (iters < 0 || !(eps >= 0.f)) return MLC_ERR_ARG;
+  if (!aligned16(in) || !aligned16(out)) return MLC_ERR_ARG;
+  const NsPlan p = make_plan(m, n);
+  rc = check_workspace(workspace, workspace_bytes, p.per_matrix);
+  if (rc != MLC_OK) return rc;
+  hipStream_t stream = (hipStream_t)stream_;
+  const int64_t chunk = chunk_for(p, workspace_bytes, count);
+  const size_t es = elem_size(io_dtype);
+  for (int64_t c0 = 0; c0 < count; c0 += chunk) {
+    const int64_t cc = count - c0 < chunk ? count - c0 : chunk;
+    const NsBuffers w = carve(p, workspace, chunk);
+    const unsigned char* src = (const unsigned char*)in + (size_t)c0 * m * n * es;
+    unsigned char* dst = (unsigned char*)out + (size_t)c0 * m * n * es;
+    rc = launch_ns_load(src, io_dtype, w.X[0], w.partials, p.nblk, cc, m, n, p.mp, p.np, stream);
+    if (rc != MLC_OK) return rc;
+    rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, eps, stream);
+    if (rc != MLC_OK) return rc;
+    int res = 0;
+    rc = run_ns_chunk(p, w, cc, iters, a, b, c, stream, &res);
+    if (rc != MLC_OK) return rc;
+    rc = launch_ns_store(w.X[res], iters == 0 ? w.scale : nullptr, dst, io_dtype, cc, m, n, p.mp,
+                         p.np, stream);
+    if (rc != MLC_OK) return rc;
+  }
+  return MLC_OK;
+}
+
+static int check_inner_groups(const mlc_inner_group* groups, int n_groups) {
+  if (!groups) return MLC_ERR_NULL;
+  if (n_groups < 0) return MLC_ERR_ARG;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_inner_group& g = groups[i];
+    if (!g.param || !g.grad || !g.momentum) return MLC_ERR_NULL;
+    if (!valid_dtype(g.param_dtype) || !valid_dtype(g.grad_dtype)) return MLC_ERR_DTYPE;
+    const int rc = check_shape(g.count, g.m, g.n);
+    if (rc != MLC_OK) return rc;
+    if (!aligned16(g.param) || !aligned16(g.grad) || !aligned16(g.momentum)) return MLC_ERR_ARG;
+  }
+  return MLC_OK;
+}
+
+size_t muloco_inner_workspace_bytes(const mlc_inner_group* groups, int n_groups) {
+  if (check_inner_groups(groups, n_groups) != MLC_OK) return 0;
+  size_t need = 0;
+  for (int i = 0; i < n_groups; ++i) {
+    const size_t b = newton_schulz_workspace_bytes(groups[i].count, groups[i].m, groups[i].n);
+    if (b > need) need = b;
+  }
+  return need;
+}
+
+size_t muloco_inner_workspace_min_bytes(const mlc_inner_group* groups, int n_groups) {
+  if (check_inner_groups(groups, n_groups) != MLC_OK) return 0;
+  size_t need = 0;
+  for (int i = 0; i < n_groups; ++i) {
+    const size_t b = newton_schulz_workspace_min_bytes(groups[i].m, groups[i].n);
+    if (b > need) need = b;
+  }
+  return need;
+}
+
+int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muon_hparams* hp,
+                      void* workspace, size_t workspace_bytes, void* stream_) {
+  if (!hp) return MLC_ERR_NULL;
+  int rc = check_inner_groups(groups, n_groups);
+  if (rc != MLC_OK) return rc;
+  if (hp->ns_iters < 0 || !(hp->ns_eps >= 0.f)) return MLC_ERR_ARG;
+  if (n_groups == 0) return MLC_OK;
+  rc = check_workspace(workspace, workspace_bytes, muloco_inner_workspace_min_bytes(groups, n_groups));
+  if (rc != MLC_OK) return rc;
+  hipStream_t stream = (hipStream_t)stream_;
+  const float decay_factor = 1.0f - hp->eta * hp->weight_decay;
+  for (int gi = 0; gi < n_groups; ++gi) {
+    const mlc_inner_group& g = groups[gi];
+    const NsPlan p = make_plan(g.m, g.n);
+    const int64_t chunk = chunk_for(p, workspace_bytes, g.count);
+    const size_t mat = (size_t)g.m * g.n;
+    for (int64_t c0 = 0; c0 < g.count; c0 += chunk) {
+      const int64_t cc = g.count - c0 < chunk ? g.count - c0 : chunk;
+      const NsBuffers w = carve(p, workspace, chunk);
+      const unsigned char* grad = (const unsigned char*)g.grad + c0 * mat * elem_size(g.grad_dtype);
+      unsigned char* param = (unsigned char*)g.param + c0 * mat * elem_size(g.param_dtype);
+      float* mom = g.momentum + c0 * mat;
+      rc = launch_momentum(grad, g.grad_dtype, mom, w.X[0], w.partials, p.nblk, cc, g.m, g.n, p.mp,
+                           p.np, hp->beta, hp->nesterov, stream);
+      if (rc != MLC_OK) return rc;
+      rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, hp->ns_eps, stream);
+      if (rc != MLC_OK) return rc;
+      int res = 0;
+      rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, stream, &res);
+      if (rc != MLC_OK) return rc;
+      rc = launch_param_update(param, g.param_dtype, w.X[res], hp->ns_iters == 0 ? w.scale : nullptr,
+                               cc, g.m, g.n, p.mp, p.np, decay_factor, hp->eta * g.lr_scale, stream);
+      if (rc != MLC_OK) return rc;
+    }
+  }
+  return MLC_OK;
+}
+
+static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
+                       bool need_update_state) {
+  if (!hp || !groups) return MLC_ERR_NULL;
+  if (n_groups < 0) return MLC_ERR_ARG;
+  if (hp->K < 1 || hp->K > MLC_MAX_WORKERS) return MLC_ERR_ARG;
+  if (hp->quant_bits != 0 && hp->quant_bits != 4)
+    return (hp->quant_bits == 2 || hp->quant_bits == 8) ? MLC_ERR_UNSUPPORTED : MLC_ERR_ARG;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_outer_group& g = groups[i];
+    if (!g.worker_params || !g.global_param) return MLC_ERR_NULL;
+    if (need_update_state && !g.outer_momentum) return MLC_ERR_NULL;
+    if (!valid_dtype(g.worker_dtype) || !valid_dtype(g.global_dtype)) return MLC_ERR_DTYPE;
+    const int rc = check_shape(g.count, g.m, g.n);
+    if (rc != MLC_OK) return rc;
+    if (!aligned16(g.global_param) || (g.outer_momentum && !aligned16(g.outer_momentum)))
+      return MLC_ERR_ARG;
+    for (int k = 0; k < hp->K; ++k) {
+      if (!g.worker_params[k]) return MLC_ERR_NULL;
+      if (!aligned16(g.worker_params[k])) return MLC_ERR_ARG;
+    }
+    if (hp->quant_bits) {
+      if (g.n % 2) return MLC_ERR_SHAPE;
+      if (!g.codes || !g.scales) return MLC_ERR_NULL;
+      for (int k = 0; k < hp->K; ++k) {
+        if (!g.codes[k] || !g.scales[k]) return MLC_ERR_NULL;
+        if (!aligned16(g.codes[k]) || !aligned16(g.scales[k])) return MLC_ERR_ARG;
+      }
+    }
+  }
+  return MLC_OK;
+}
+
+static void gather_ptrs(const mlc_outer_group& g, int K, bool quant, WorkerPtrs& w, CodePtrs& c,
+                        ScalePtrs& s) {
+  for (int k = 0; k < MLC_MAX_WORKERS; ++k) {
+    w.p[k] = k < K ? g.worker_params[k] : nullptr;
+    c.p[k] = (quant && k < K) ? g.codes[k] : nullptr;
+    s.p[k] = (quant && k < K) ? g.scales[k] : nullptr;
+  }
+}
+
+int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
+                          void* stream_) {
+  int rc = check_outer(groups, n_groups, hp, false);
+  if (rc != MLC_OK) return rc;
+  if (hp->quant_bits != 4) return MLC_ERR_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_outer_group& g = groups[i];
+    WorkerPtrs w; CodePtrs c; ScalePtrs s;
+    gather_ptrs(g, hp->K, true, w, c, s);
+    rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, g.count * g.m, g.n,
+                         hp->K, stream);
+    if (rc != MLC_OK) return rc;
+  }
+  return MLC_OK;
+}
+
+int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
+                      void* stream_) {
+  int rc = check_outer(groups, n_groups, hp, true);
+  if (rc != MLC_OK) return rc;
+  hipStream_t stream = (hipStream_t)stream_;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_outer_group& g = groups[i];
+    WorkerPtrs w; CodePtrs c; ScalePtrs s;
+    gather_ptrs(g, hp->K, hp->quant_bits != 0, w, c, s);
+    if (hp->quant_bits) {
+      rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, g.count * g.m,
+                           g.n, hp->K, stream);
+      if (rc != MLC_OK) return rc;
+      rc = launch_dequant_outer(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
+                                c, s, g.count * g.m, g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
+                                hp->write_back, stream);
+    } else {
+      rc = launch_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
+                              g.count * g.m * g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
+                              hp->write_back, stream);
+    }
+    if (rc != MLC_OK) return rc;
+  }
+  return MLC_OK;
+}
+
+int muloco_timing_enable(int on) {
+  TimingState& t = timing();
+  std::lock_guard<std::mutex> lock(t.mu);
+  t.enabled = on != 0;
+  return MLC_OK;
+}
+
+int muloco_timing_read(mlc_kernel_timing* out) {
+  if (!out) return MLC_ERR_NULL;
+  TimingState& t = timing();
+  std::lock_guard<std::mutex> lock(t.mu);
+  for (int i = 0; i < MLC_KERNEL_FAMILIES; ++i) out[i] = mlc_kernel_timing{0, 0.0, 0.0, 0.0};
+  int rc = MLC_OK;
+  for (const TimingRecord& r : t.records) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess ||
+        hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
+      rc = MLC_ERR_LAUNCH;
+    } else if (r.family >= 0 && r.family < MLC_KERNEL_FAMILIES) {
+      out[r.family].launches += 1;
+      out[r.family].total_ms += ms;
+      out[r.family].flops += r.flops;
+      out[r.family].bytes += r.bytes;
+    }
+    t.pool.push_back(r.start);
+    t.pool.push_back(r.stop);
+  }
+  t.records.clear();
+  return rc;
+}
+
+}  // extern "C"

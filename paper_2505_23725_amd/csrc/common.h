@@ -1,0 +1,101 @@
+// Shared declarations of the MuLoCo HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/muloco.h"
+
+namespace mlc {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(((unsigned int)v) << 16);
+}
+// Round to nearest, ties to even.  NaN keeps a quiet-NaN pattern.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned int u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+  return (unsigned int)f32_to_bf16(lo) | ((unsigned int)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ float bf16lo(unsigned int w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(unsigned int w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+static inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
+
+// ---- timing recorder -------------------------------------------------------------
+struct LaunchScope {
+  LaunchScope(int family, hipStream_t stream, double flops, double bytes);
+  ~LaunchScope();
+  int slot;
+  hipStream_t stream;
+};
+
+// ---- batched bf16 GEMM of Newton-Schulz (ns_gemm.hip) ------------------------------
+// D[b] = alpha_b * op(A[b]) * op(B[b])^T + beta * C[b] + gamma * I, all bf16, fp32 accum.
+// Operand A is M x K, operand B is N x K.  An operand is either K-contiguous (element
+// (i,k) at ptr[i*ld + k]) or K-strided (element (i,k) at ptr[k*ld + i]).
+// M and N must be multiples of 128, K a multiple of 64; all leading dimensions and batch
+// strides multiples of 8 elements.
+struct GemmDesc {
+  const bf16_t* A; int64_t lda, strideA; int a_kstrided;
+  const bf16_t* B; int64_t ldb, strideB; int b_kstrided;
+  bf16_t* D; int64_t ldd, strideD;
+  const bf16_t* C; int64_t ldc, strideC;   // may be null (beta ignored)
+  int M, N, K, batch;
+  float alpha, beta, gamma;
+  const float* bscale;   // optional per-batch factor
+  int bscale_pow;        // alpha_b = alpha * bscale[b]^bscale_pow (pow in {1,2})
+};
+int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
+
+// ---- elementwise kernels of the inner step (inner_elementwise.hip) ----------------
+int launch_momentum(const void* grad, int grad_dtype, float* mom, bf16_t* U, float* partials,
+                    int nblk, int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
+                    float beta, int nesterov, hipStream_t stream);
+int launch_ns_load(const void* in, int dtype, bf16_t* U, float* partials, int nblk,
+                   int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
+                   hipStream_t stream);
+int launch_norm_finalize(const float* partials, int nblk, float* scale, int64_t count,
+                         float eps, hipStream_t stream);
+int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale,
+                        int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
+                        float decay_factor, float step, hipStream_t stream);
+int launch_ns_store(const bf16_t* X, const float* oscale, void* out, int dtype, int64_t count,
+                    int64_t m, int64_t n, int64_t mp, int64_t np, hipStream_t stream);
+
+// ---- outer step kernels (outer.hip) ----------------------------------------------
+struct WorkerPtrs { void* p[MLC_MAX_WORKERS]; };
+struct CodePtrs { uint8_t* p[MLC_MAX_WORKERS]; };
+struct ScalePtrs { float* p[MLC_MAX_WORKERS]; };
+int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
+                       float* u, int64_t n_elems, int K, float eta_out, float mu, int nesterov,
+                       int write_back, hipStream_t stream);
+int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
+                    const CodePtrs& codes, const ScalePtrs& scales, int64_t rows, int64_t n,
+                    int K, hipStream_t stream);
+int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
+                         float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
+                         int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
+                         hipStream_t stream);
+
+}  // namespace mlc

@@ -1,0 +1,148 @@
+"""Device-side bookkeeping for running the MuLoCo hot path on a synthetic workload.
+
+Owns the torch tensors (parameters of K worker replicas, Muon momentum, gradients, the
+global copy and the outer momentum, quantiser outputs, the work space) and builds the
+group descriptors the C-ABI calls take.  It performs no optimizer arithmetic: every
+update happens inside libmuloco.so.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional
+
+import torch
+
+import synth_inputs as S
+from . import binding as B
+
+
+class MulocoJob:
+    def __init__(self, workload: S.Workload, device="cuda:0", seed: int = 0,
+                 layers: Optional[int] = None, K: Optional[int] = None,
+                 with_quant: bool = False, workspace_cap_bytes: Optional[int] = None,
+                 grad_dtype: Optional[torch.dtype] = None, generate_on: str = "cpu"):
+        """generate_on: "cpu" draws every tensor with the CPU generator and copies it over
+        (reproducible on the host for parity tests); "device" draws on the GPU (full-size
+        workloads)."""
+        self.wl = workload
+        self.device = torch.device(device)
+        self.seed = seed
+        self.K = workload.K if K is None else K
+        L = workload.layers if layers is None else layers
+        d, f = workload.d_model, workload.d_ffn
+        self.shapes = [(4 * L, d, d), (L, d, f), (L, f, d)]
+        self.pdtype = S.torch_dtype(workload.param_dtype)
+        self.gdtype = grad_dtype or self.pdtype
+        self.gen_dev = "cpu" if generate_on == "cpu" else self.device
+        self.theta_g: List[torch.Tensor] = []
+        self.u: List[torch.Tensor] = []
+        self.workers: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
+        self.mom: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
+        self.grad: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
+        for gi, shp in enumerate(self.shapes):
+            init = self._draw(shp, S.PARAM_STD, 100 + gi, self.pdtype)   # theta^(0), worker dtype
+            self.theta_g.append(init.to(torch.float32))
+            self.u.append(torch.zeros(shp, dtype=torch.float32, device=self.device))
+            for k in range(self.K):
+                self.workers[k].append(init.clone())
+                self.mom[k].append(torch.zeros(shp, dtype=torch.float32, device=self.device))
+                self.grad[k].append(torch.zeros(shp, dtype=self.gdtype, device=self.device))
+        self.codes = self.scales = None
+        if with_quant:
+            self.codes = [[torch.empty((c * m, n // 2), dtype=torch.uint8, device=self.device)
+                           for (c, m, n) in self.shapes] for _ in range(self.K)]
+            self.scales = [[torch.empty((c * m,), dtype=torch.float32, device=self.device)
+                            for (c, m, n) in self.shapes] for _ in range(self.K)]
+        need = max(B.newton_schulz_workspace_bytes(*s) for s in self.shapes)
+        floor = max(B.newton_schulz_workspace_min_bytes(s[1], s[2]) for s in self.shapes)
+        if workspace_cap_bytes is not None:
+            need = max(floor, min(need, workspace_cap_bytes))
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+
+    # -- synthetic draws --------------------------------------------------------------
+    def _draw(self, shape, std, stream, dtype):
+        return S.normal(shape, std, self.seed, stream, device=self.gen_dev, dtype=dtype).to(self.device)
+
+    def grad_stream(self, k: int, step: int, gi: int) -> int:
+        return 10_000 + (step * 64 + k) * 8 + gi
+
+    def draw_gradients(self, step: int) -> None:
+        """Fresh i.i.d. gradients for every replica: g ~ 1e-3 N(0,1), keyed by (k, step, group)."""
+        for k in range(self.K):
+            for gi, shp in enumerate(self.shapes):
+                self.grad[k][gi].copy_(self._draw(shp, S.GRAD_STD, self.grad_stream(k, step, gi), self.gdtype))
+
+    def displace_workers(self, std: float = S.DELTA_STD) -> None:
+        """theta_k = theta_g - Delta_k with Delta_k ~ std N(0,1): stands in for H inner steps
+        when only the outer step is exercised."""
+        for k in range(self.K):
+            for gi, shp in enumerate(self.shapes):
+                delta = self._draw(shp, std, 5_000 + k * 8 + gi, torch.float32)
+                self.workers[k][gi].copy_((self.theta_g[gi] - delta).to(self.pdtype))
+
+    # -- descriptors --------------------------------------------------------------------
+    @staticmethod
+    def lr_scale(m: int, n: int) -> float:
+        """Paper Sec. 5 "MuLoCo": rescale the learning rate by sqrt(n/m) for an m x n matrix."""
+        return math.sqrt(n / m)
+
+    def inner_groups(self, k: int) -> List[B.InnerGroup]:
+        return [B.InnerGroup(self.workers[k][gi], self.grad[k][gi], self.mom[k][gi],
+                             self.lr_scale(m, n))
+                for gi, (c, m, n) in enumerate(self.shapes)]
+
+    def outer_groups(self, quant: bool = False, group_ids=None) -> List[B.OuterGroup]:
+        ids = range(len(self.shapes)) if group_ids is None else group_ids
+        out = []
+        for gi in ids:
+            ws = [self.workers[k][gi] for k in range(self.K)]
+            if quant:
+                out.append(B.OuterGroup(ws, self.theta_g[gi], self.u[gi],
+                                        [self.codes[k][gi] for k in range(self.K)],
+                                        [self.scales[k][gi] for k in range(self.K)]))
+            else:
+                out.append(B.OuterGroup(ws, self.theta_g[gi], self.u[gi]))
+        return out
+
+    def layer_fragment(self, layer: int, quant: bool = False) -> List[B.OuterGroup]:
+        """Outer-step groups covering one transformer layer (4 d x d, one d x f, one f x d):
+        the unit a streaming schedule synchronises at a time."""
+        out = []
+        for gi, (c, m, n) in enumerate(self.shapes):
+            per_layer = 4 if gi == 0 else 1
+            sl = slice(layer * per_layer, (layer + 1) * per_layer)
+            ws = [self.workers[k][gi][sl] for k in range(self.K)]
+            if quant:
+                rows = slice(layer * per_layer * m, (layer + 1) * per_layer * m)
+                out.append(B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl],
+                                        [self.codes[k][gi][rows] for k in range(self.K)],
+                                        [self.scales[k][gi][rows] for k in range(self.K)]))
+            else:
+                out.append(B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl]))
+        return out
+
+    def muon_hparams(self) -> B.MuonHParams:
+        return B.MuonHParams(eta=self.wl.eta_in, weight_decay=self.wl.weight_decay, beta=self.wl.beta,
+                             nesterov=True)
+
+    def outer_hparams(self, quant_bits: int = 0, write_back: bool = True) -> B.OuterHParams:
+        return B.OuterHParams(K=self.K, eta_out=self.wl.eta_out, mu=self.wl.mu, nesterov=True,
+                              quant_bits=quant_bits, write_back=write_back)
+
+    # -- the hot path -----------------------------------------------------------------------
+    def inner_step(self) -> None:
+        hp = self.muon_hparams()
+        for k in range(self.K):
+            B.muloco_inner_step(self.inner_groups(k), hp, self.workspace)
+
+    def outer_step(self, quant_bits: int = 0) -> None:
+        B.muloco_outer_step(self.outer_groups(quant=quant_bits != 0), self.outer_hparams(quant_bits))
+
+    def ns_flops(self, iters: int = 5) -> float:
+        """Matrix-core FLOP the library executes for one inner step of one replica."""
+        tot = 0.0
+        for (c, m, n) in self.shapes:
+            mp, np_ = -(-m // 128) * 128, -(-n // 128) * 128
+            s, l = min(mp, np_), max(mp, np_)
+            tot += c * iters * (4.0 * s * s * l + 2.0 * s ** 3)
+        return tot

@@ -1,0 +1,149 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every function the
+header declares, and its host-side validation rejects bad arguments before touching the
+GPU (none of these calls enqueues work)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2505_23725_amd as mlc
+from paper_2505_23725_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "muloco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{}]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mlc.library()
+    names = _declared_functions()
+    assert {"newton_schulz", "muloco_inner_step", "muloco_outer_step", "muloco_quantize_delta",
+            "muloco_strerror", "newton_schulz_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in muloco.h but not exported"
+
+
+def test_strerror_and_codes():
+    assert mlc.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert mlc.strerror(code) not in ("ok", "unknown error")
+    assert mlc.strerror(-99) == "unknown error"
+
+
+def test_workspace_sizes():
+    one = mlc.newton_schulz_workspace_min_bytes(2048, 2048)
+    # two X buffers + Gram + polynomial, bf16, plus small per-matrix slots
+    assert one >= 4 * 2048 * 2048 * 2
+    assert one < 4 * 2048 * 2048 * 2 + 16384
+    assert mlc.newton_schulz_workspace_bytes(96, 2048, 2048) == 96 * one
+    # padding to the 128 tile granularity
+    assert mlc.newton_schulz_workspace_min_bytes(100, 130) == mlc.newton_schulz_workspace_min_bytes(128, 256)
+    # tall and wide need the same space
+    assert mlc.newton_schulz_workspace_min_bytes(512, 128) == mlc.newton_schulz_workspace_min_bytes(128, 512)
+    assert mlc.newton_schulz_workspace_bytes(0, 8, 8) == 0
+    assert mlc.newton_schulz_workspace_min_bytes(-1, 8) == 0
+
+
+def _ns(lib, inp=0x1000, out=0x1000, dtype=0, count=1, m=128, n=128, iters=5, ws=0x10000, wsb=1 << 30, eps=1e-7):
+    return lib.newton_schulz(inp, out, dtype, count, m, n, iters, 3.4445, -4.775, 2.0315, eps, ws, wsb, None)
+
+
+def test_newton_schulz_argument_errors():
+    lib = mlc.library()
+    assert _ns(lib, inp=None) == -1
+    assert _ns(lib, out=None) == -1
+    assert _ns(lib, dtype=7) == -3
+    assert _ns(lib, count=0) == -2
+    assert _ns(lib, m=0) == -2
+    assert _ns(lib, n=-4) == -2
+    assert _ns(lib, m=1 << 31) == -2
+    assert _ns(lib, iters=-1) == -5
+    assert _ns(lib, eps=-1.0) == -5
+    assert _ns(lib, inp=0x1004) == -5                 # misaligned data pointer
+    assert _ns(lib, ws=None) == -4
+    assert _ns(lib, ws=0x10010) == -4                 # work space not 256-byte aligned
+    assert _ns(lib, wsb=1024) == -4                   # too small for one matrix
+
+
+def _inner_group(**kw):
+    d = dict(count=2, m=128, n=256, param=0x1000, param_dtype=1, grad=0x2000, grad_dtype=1,
+             momentum=0x3000, lr_scale=1.0)
+    d.update(kw)
+    return B._InnerGroup(**d)
+
+
+def test_inner_step_argument_errors():
+    lib = mlc.library()
+    hp = B._MuonHParams(0.05, 0.01, 0.95, 1, 5, 3.4445, -4.775, 2.0315, 1e-7)
+
+    def call(g, hp_=hp, ws=0x10000, wsb=1 << 30, n=1):
+        arr = (B._InnerGroup * 1)(g)
+        return lib.muloco_inner_step(arr, n, C.byref(hp_) if hp_ is not None else None, ws, wsb, None)
+
+    assert call(_inner_group(param=None)) == -1
+    assert call(_inner_group(grad=None)) == -1
+    assert call(_inner_group(momentum=None)) == -1
+    assert call(_inner_group(), hp_=None) == -1
+    assert call(_inner_group(param_dtype=3)) == -3
+    assert call(_inner_group(count=0)) == -2
+    assert call(_inner_group(), wsb=100) == -4
+    assert call(_inner_group(), ws=None) == -4
+    assert call(_inner_group(), n=-1) == -5
+    bad = B._MuonHParams(0.05, 0.01, 0.95, 1, -2, 3.4445, -4.775, 2.0315, 1e-7)
+    assert call(_inner_group(), hp_=bad) == -5
+    arr = (B._InnerGroup * 1)(_inner_group())
+    assert lib.muloco_inner_step(arr, 0, C.byref(hp), None, 0, None) == 0     # nothing to do
+    assert lib.muloco_inner_workspace_bytes(arr, 1) == 2 * mlc.newton_schulz_workspace_min_bytes(128, 256)
+    assert lib.muloco_inner_workspace_min_bytes(arr, 1) == mlc.newton_schulz_workspace_min_bytes(128, 256)
+
+
+def test_outer_step_argument_errors():
+    lib = mlc.library()
+    K = 2
+    wp = (C.c_void_p * K)(0x1000, 0x2000)
+    cp = (C.c_void_p * K)(0x5000, 0x6000)
+    sp = (C.c_void_p * K)(0x7000, 0x8000)
+
+    def group(**kw):
+        d = dict(count=1, m=4, n=16, worker_params=C.cast(wp, C.POINTER(C.c_void_p)), worker_dtype=1,
+                 global_param=0x3000, global_dtype=0, outer_momentum=0x4000,
+                 codes=C.cast(cp, C.POINTER(C.c_void_p)), scales=C.cast(sp, C.POINTER(C.c_void_p)))
+        d.update(kw)
+        return B._OuterGroup(**d)
+
+    def call(g, fn="muloco_outer_step", **hpkw):
+        h = dict(K=K, eta_out=0.7, mu=0.9, nesterov=1, quant_bits=0, write_back=1)
+        h.update(hpkw)
+        hp = B._OuterHParams(**h)
+        arr = (B._OuterGroup * 1)(g)
+        return getattr(lib, fn)(arr, 1, C.byref(hp), None)
+
+    assert call(group(global_param=None)) == -1
+    assert call(group(outer_momentum=None)) == -1
+    assert call(group(worker_params=None)) == -1
+    assert call(group(), K=0) == -5
+    assert call(group(), K=33) == -5
+    assert call(group(), quant_bits=3) == -5
+    assert call(group(), quant_bits=8) == -7          # named by the paper, not built yet
+    assert call(group(worker_dtype=9)) == -3
+    assert call(group(m=0)) == -2
+    assert call(group(n=15), quant_bits=4) == -2      # odd row length cannot be packed
+    assert call(group(codes=None), quant_bits=4) == -1
+    assert call(group(), fn="muloco_quantize_delta", quant_bits=0) == -5
+    null_worker = (C.c_void_p * K)(0x1000, None)
+    assert call(group(worker_params=C.cast(null_worker, C.POINTER(C.c_void_p)))) == -1
+
+
+def test_binding_rejects_cpu_tensors_and_bad_dtypes():
+    import torch
+    x = torch.zeros(4, 4)
+    with pytest.raises(ValueError):
+        mlc.newton_schulz(x, x, torch.zeros(16, dtype=torch.uint8))
+    with pytest.raises(TypeError):
+        B._dtype_code(torch.zeros(2, dtype=torch.float16))

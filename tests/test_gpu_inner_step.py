@@ -1,0 +1,119 @@
+"""GPU parity: muloco_inner_step (C-ABI) against the fp64 oracle on seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_23725_amd as mlc
+import synth_inputs as S
+from oracle import muon, storage
+from helpers import EW_TOL, NS_TOL, assert_fp32_close, dtype_name, rel_fro, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _make_group(cnt, m, n, pdtype, gdtype, seed, zero_momentum=False):
+    W = S.normal((cnt, m, n), S.PARAM_STD, seed, 1, dtype=pdtype)
+    g = S.normal((cnt, m, n), S.GRAD_STD, seed, 2, dtype=gdtype)
+    mom = S.normal((cnt, m, n), 3 * S.GRAD_STD, seed, 3, dtype=torch.float32)
+    if zero_momentum:
+        mom.zero_()
+    return W, g, mom
+
+
+def _oracle_group(W, g, mom, hp: mlc.MuonHParams, lr_scale):
+    Wn, mn, On = [], [], []
+    for i in range(W.shape[0]):
+        w1, m1, o1 = muon.inner_step(to_f64(W[i]), to_f64(mom[i]), to_f64(g[i]), eta=hp.eta,
+                                     weight_decay=hp.weight_decay, beta=hp.beta, nesterov=hp.nesterov,
+                                     ns_iters=hp.ns_iters, coeffs=(hp.ns_a, hp.ns_b, hp.ns_c),
+                                     eps=hp.ns_eps, lr_scale=lr_scale)
+        Wn.append(w1); mn.append(m1); On.append(o1)
+    return np.stack(Wn), np.stack(mn), np.stack(On)
+
+
+def _check_group(W0, g, mom0, W1, mom1, hp, lr_scale, what):
+    Wr, mr, Or = _oracle_group(W0, g, mom0, hp, lr_scale)
+    assert_fp32_close(mom1, mr, f"{what}: momentum")
+    W0f, W1f = to_f64(W0), to_f64(W1)
+    for i in range(W0.shape[0]):
+        # compare the update, never the weights (the weights would hide any error)
+        upd_ref = Wr[i] - W0f[i]
+        upd_gpu = W1f[i] - W0f[i]
+        slack = 0.0
+        if W1.dtype == torch.bfloat16:   # storing W in bf16 adds up to half an ulp per element
+            slack = np.linalg.norm(storage.bf16_ulp(Wr[i]) * 0.5) / np.linalg.norm(upd_ref)
+        err = rel_fro(upd_gpu, upd_ref)
+        assert err <= NS_TOL + slack, f"{what}: matrix {i} update error {err:.3e} (slack {slack:.2e})"
+
+
+CASES = [
+    # cnt, m, n, param dtype, grad dtype
+    (2, 128, 128, torch.float32, torch.float32),
+    (2, 128, 512, torch.float32, torch.float32),
+    (2, 512, 128, torch.float32, torch.float32),
+    (3, 256, 384, torch.bfloat16, torch.bfloat16),
+    (2, 200, 136, torch.bfloat16, torch.float32),
+    (1, 333, 77, torch.float32, torch.bfloat16),
+    (2, 768, 768, torch.bfloat16, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("cnt,m,n,pd,gd", CASES)
+@pytest.mark.parametrize("nesterov", [True, False])
+def test_inner_step_matches_oracle(cnt, m, n, pd, gd, nesterov):
+    hp = mlc.MuonHParams(eta=6.25e-2, weight_decay=1.25e-3, beta=0.95, nesterov=nesterov)
+    lr_scale = math.sqrt(n / m)
+    W0, g, mom0 = _make_group(cnt, m, n, pd, gd, seed=m + n)
+    W, gg, mom = W0.to(DEV), g.to(DEV), mom0.to(DEV)
+    grp = mlc.InnerGroup(W, gg, mom, lr_scale)
+    ws = torch.empty(mlc.muloco_inner_workspace_bytes([grp]), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step([grp], hp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gg.cpu().view(torch.int16 if gd == torch.bfloat16 else torch.int32),
+                       g.view(torch.int16 if gd == torch.bfloat16 else torch.int32)), "gradient was modified"
+    _check_group(W0, g, mom0, W.cpu(), mom.cpu(), hp, lr_scale, f"{cnt}x{m}x{n} {dtype_name(W0)}")
+
+
+def test_several_groups_one_call_and_small_work_space():
+    hp = mlc.MuonHParams(eta=0.05, weight_decay=0.01, beta=0.9)
+    shapes = [(4, 128, 128), (2, 128, 512), (2, 512, 128)]
+    host, dev = [], []
+    for i, (c, m, n) in enumerate(shapes):
+        W0, g, m0 = _make_group(c, m, n, torch.bfloat16, torch.bfloat16, seed=10 + i)
+        host.append((W0, g, m0))
+        dev.append(mlc.InnerGroup(W0.to(DEV), g.to(DEV), m0.to(DEV), math.sqrt(n / m)))
+    ws = torch.empty(mlc.muloco_inner_workspace_min_bytes(dev), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step(dev, hp, ws)
+    torch.cuda.synchronize()
+    for (W0, g, m0), grp, (c, m, n) in zip(host, dev, shapes):
+        _check_group(W0, g, m0, grp.param.cpu(), grp.momentum.cpu(), hp, math.sqrt(n / m), f"group {m}x{n}")
+
+
+def test_zero_gradient_and_momentum_only_decays():
+    hp = mlc.MuonHParams(eta=0.1, weight_decay=0.05, beta=0.9)
+    W0 = S.normal((1, 128, 256), S.PARAM_STD, 0, 7, dtype=torch.float32)
+    W = W0.to(DEV)
+    g = torch.zeros_like(W)
+    mom = torch.zeros_like(W)
+    grp = mlc.InnerGroup(W, g, mom, 1.0)
+    ws = torch.empty(mlc.muloco_inner_workspace_bytes([grp]), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step([grp], hp, ws)
+    torch.cuda.synchronize()
+    ref = to_f64(W0) * (1 - 0.1 * 0.05)
+    assert_fp32_close(W.cpu(), ref, "decay only")
+    assert torch.count_nonzero(mom) == 0
+
+
+def test_zero_iterations_uses_normalised_direction():
+    hp = mlc.MuonHParams(eta=0.1, weight_decay=0.0, beta=0.5, ns_iters=0)
+    W0, g, m0 = _make_group(1, 128, 128, torch.float32, torch.float32, seed=77)
+    grp = mlc.InnerGroup(W0.to(DEV), g.to(DEV), m0.to(DEV), 1.0)
+    ws = torch.empty(mlc.muloco_inner_workspace_bytes([grp]), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step([grp], hp, ws)
+    torch.cuda.synchronize()
+    Wr, mr, _ = _oracle_group(W0, g, m0, hp, 1.0)
+    upd = to_f64(grp.param.cpu()) - to_f64(W0)
+    assert rel_fro(upd, Wr - to_f64(W0)) <= 4e-3      # bf16 rounding of the direction only

@@ -1,0 +1,55 @@
+"""GPU parity on the smallest workload, whole: a 2-layer d=128 / FFN 512 fp32 parameter set,
+K = 1, H = 8 Muon steps (momentum 0.95, Nesterov, 5 Newton-Schulz iterations) with a fresh
+seeded gradient per step, then one outer Nesterov step (lr 0.7, momentum 0.9).  The oracle
+runs the same trajectory in fp64 from the same seeded draws."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import diloco, muon
+from helpers import NS_TOL, assert_fp32_close, rel_fro, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_workload_h8_then_outer_step():
+    from paper_2505_23725_amd.harness import MulocoJob
+    wl = S.WORKLOADS["tiny"]
+    job = MulocoJob(wl, generate_on="cpu", seed=0)
+    theta0 = [t.cpu().clone() for t in job.theta_g]
+    for h in range(wl.H):
+        job.draw_gradients(h)
+        job.inner_step()
+    torch.cuda.synchronize()
+    W_gpu = [w.cpu() for w in job.workers[0]]
+    m_gpu = [m.cpu() for m in job.mom[0]]
+    job.outer_step()
+    torch.cuda.synchronize()
+
+    worst = 0.0
+    for gi, (cnt, m, n) in enumerate(job.shapes):
+        th0 = to_f64(S.normal((cnt, m, n), S.PARAM_STD, 0, 100 + gi))
+        assert np.array_equal(th0, to_f64(theta0[gi]))
+        W = th0.copy()
+        mom = np.zeros_like(W)
+        for h in range(wl.H):
+            g = to_f64(S.normal((cnt, m, n), S.GRAD_STD, 0, job.grad_stream(0, h, gi)))
+            for i in range(cnt):
+                W[i], mom[i], _ = muon.inner_step(W[i], mom[i], g[i], eta=wl.eta_in,
+                                                  weight_decay=wl.weight_decay, beta=wl.beta,
+                                                  nesterov=True, lr_scale=job.lr_scale(m, n))
+        assert_fp32_close(m_gpu[gi], mom, f"group {gi}: momentum after H steps")
+        for i in range(cnt):
+            err = rel_fro(to_f64(W_gpu[gi][i]) - th0[i], W[i] - th0[i])
+            worst = max(worst, err)
+            assert err <= NS_TOL, f"group {gi} matrix {i}: displacement error {err:.3e}"
+        # outer step: oracle on its own trajectory
+        out = diloco.outer_step(th0.reshape(-1, n), np.zeros((cnt * m, n)), [W.reshape(-1, n)],
+                                eta_out=wl.eta_out, mu=wl.mu)
+        u_gpu = to_f64(job.u[gi].cpu()).reshape(-1, n)
+        th_gpu = to_f64(job.theta_g[gi].cpu()).reshape(-1, n)
+        assert rel_fro(u_gpu, out["u"]) <= NS_TOL
+        assert rel_fro(th_gpu - th0.reshape(-1, n), out["theta"] - th0.reshape(-1, n)) <= NS_TOL
+        assert torch.equal(job.workers[0][gi], job.theta_g[gi]), "write-back must copy theta_g"
+    print(f"tiny workload: worst displacement error after H={wl.H} steps {worst:.3e}")
