@@ -39,28 +39,27 @@ def cpu_baseline(workload, budget_s: float):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    shapes = []
     d, f = workload.d_model, workload.d_ffn
-    for (m, n) in [(d, d), (d, f)]:
-        shapes.append((min(m, 2048), min(n, 8192)))
+    shapes = [(min(d, 2048), min(d, 2048)), (min(d, 2048), min(f, 8192))]
     flops = 0.0
     t_used = 0.0
-    done = []
-    for (m, n) in shapes:
-        g = S.normal((m, n), S.GRAD_STD, 0, 999).numpy().astype(np.float64)
+    done = {}
+    i = 0
+    # alternate over the workload's shapes (capped at 2048 x 8192) until the budget is used
+    while t_used < budget_s and i < 64:
+        m, n = shapes[i % len(shapes)]
+        g = S.normal((m, n), S.GRAD_STD, 0, 999 + i).numpy().astype(np.float64)
         t0 = time.perf_counter()
         muon.newton_schulz(g, 5)
-        dt = time.perf_counter() - t0
-        s, l = min(m, n), max(m, n)
-        # the oracle always uses the m x m Gram form: 2 m^2 n + 2 m^3 + 2 m^2 n per iteration
+        t_used += time.perf_counter() - t0
+        # the oracle always uses the m x m Gram form: 4 m^2 n + 2 m^3 FLOP per iteration
         flops += 5 * (4.0 * m * m * n + 2.0 * m ** 3)
-        t_used += dt
-        done.append(f"{m}x{n}")
-        if t_used > budget_s:
-            break
+        done[f"{m}x{n}"] = done.get(f"{m}x{n}", 0) + 1
+        i += 1
+    sample = ", ".join(f"{c} of {k}" for k, c in done.items())
     return {"value": flops / t_used * 1e-12, "unit": "TFLOP/s", "cores": int(cores),
             "kind": "oracle",
-            "sample": "fp64 NumPy Newton-Schulz (5 iterations) on one matrix each of " + ", ".join(done),
+            "sample": "fp64 NumPy Newton-Schulz (5 iterations) on matrices drawn like the workload's: " + sample,
             "seconds": round(t_used, 2)}
 
 
@@ -71,7 +70,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="1.76b", help="tiny | 150m | 1.76b | 3.1b | 15b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--workspace-gb", type=float, default=None)
     args = ap.parse_args()
     if args.gpus != 1:

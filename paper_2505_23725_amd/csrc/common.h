@@ -16,15 +16,17 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
   return __uint_as_float(((unsigned int)v) << 16);
 }
-// Round to nearest, ties to even.  NaN keeps a quiet-NaN pattern.
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  unsigned int u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// fp32 -> bf16, round to nearest, ties to even (v_cvt_pk_bf16_f32 on gfx950).
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
-  return (unsigned int)f32_to_bf16(lo) | ((unsigned int)f32_to_bf16(hi) << 16);
+  f32x2_t v;
+  v.x = lo;
+  v.y = hi;
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu);
 }
 __device__ __forceinline__ float bf16lo(unsigned int w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(unsigned int w) { return __uint_as_float(w & 0xffff0000u); }
@@ -54,7 +56,7 @@ struct LaunchScope {
 // D[b] = alpha_b * op(A[b]) * op(B[b])^T + beta * C[b] + gamma * I, all bf16, fp32 accum.
 // Operand A is M x K, operand B is N x K.  An operand is either K-contiguous (element
 // (i,k) at ptr[i*ld + k]) or K-strided (element (i,k) at ptr[k*ld + i]).
-// M and N must be multiples of 128, K a multiple of 64; all leading dimensions and batch
+// M, N and K must be multiples of 128; all leading dimensions and batch
 // strides multiples of 8 elements.
 struct GemmDesc {
   const bf16_t* A; int64_t lda, strideA; int a_kstrided;
