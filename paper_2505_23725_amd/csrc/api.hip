@@ -136,22 +136,25 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
     g.M = (int)p.sp; g.N = (int)p.sp; g.K = (int)(wide ? p.np : p.mp); g.batch = (int)chunk;
     g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
     g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 2;
+    g.symmetric = 1;     // only the lower triangle of tiles is computed, then mirrored
     int rc = launch_ns_gemm(g, stream);
     if (rc != MLC_OK) return rc;
-    // Polynomial: B' = c A A + b A + a I   (A symmetric, so A A^T = A A)
+    // Polynomial: B' = c A A + b A + a I.  A is symmetric, so either operand may be read
+    // along rows or along columns; the K-strided LDS path is the faster one.
     g = GemmDesc{};
-    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
-    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
+    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 1;
+    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 1;
     g.D = w.B; g.ldd = p.sp; g.strideD = ss;
     g.C = w.A; g.ldc = p.sp; g.strideC = ss;
     g.M = g.N = g.K = (int)p.sp; g.batch = (int)chunk;
     g.alpha = c; g.beta = b; g.gamma = a;
+    g.symmetric = 1;
     rc = launch_ns_gemm(g, stream);
     if (rc != MLC_OK) return rc;
     // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
     g = GemmDesc{};
-    if (wide) {
-      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
+    if (wide) {     // B' symmetric: read it K-strided like X, which has k as its slow index
+      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 1;
       g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = 1;
       g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
     } else {

@@ -67,6 +67,8 @@ struct GemmDesc {
   float alpha, beta, gamma;
   const float* bscale;   // optional per-batch factor
   int bscale_pow;        // alpha_b = alpha * bscale[b]^bscale_pow (pow in {1,2})
+  int symmetric;         // the result is symmetric (M == N): compute the lower triangle of
+                         // tiles and store each off-diagonal tile twice
 };
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
 

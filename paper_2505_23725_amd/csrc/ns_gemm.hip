@@ -36,10 +36,24 @@ struct GemmArgs {
   bf16_t* D; long ldd, strideD;
   const bf16_t* C; long ldc, strideC;
   int K, batch;
-  int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
+  int tiles_m, tiles_n, tiles_per_mat, total_tiles, tiles_per_xcd, wg_per_xcd;
+  int symmetric;
   float alpha, beta, gamma;
   const float* bscale; int bscale_pow;
 };
+
+// K-contiguous stage layout: [R row slots][8 chunks of 16 B].  The LDS has 64 four-byte
+// banks and serves a 128-bit read 16 lanes at a time, so the 16 chunks read by lanes
+// 0-15 (same k chunk, rows TT apart) must land on 16 different 16-byte columns of the
+// 256-byte bank line.  Row r therefore lives in slot kc_slot(r) = r with bit 0 and bit
+// log2(TT) exchanged (rows TT apart alternate between the two 128-byte halves), and chunk c
+// of row r sits at position c ^ ((r / (2 TT)) & 7) inside the slot.
+template <int TT>
+__device__ __forceinline__ int kc_slot(int row) {
+  constexpr int HB = TT == 4 ? 2 : 1;             // log2(TT)
+  const int b0 = row & 1, bh = (row >> HB) & 1;
+  return (row & ~(1 | (1 << HB))) | (b0 << HB) | bh;
+}
 
 // ---- global -> register staging of one operand tile (R rows x 64 k) -----------------
 // Loads go through a raw buffer resource on the matrix (base in SGPRs, one 32-bit lane
@@ -51,6 +65,7 @@ struct TileLoader {
   static constexpr int CPR = R / 8;             // chunks per k-row when K-strided
   __amdgpu_buffer_rsrc_t rsrc;                  // the matrix (at most 4 GiB)
   unsigned int voff;                            // lane's byte offset of its first chunk, k = 0
+  unsigned int voff_odd;                        // same for odd chunk indices (K-contiguous, TT = 4)
   unsigned int it_stride;                       // bytes between a thread's chunks
   unsigned int k_stride;                        // bytes per K step
   int lds_off;                                  // byte offset of the first chunk in the stage
@@ -60,21 +75,30 @@ struct TileLoader {
   __device__ __forceinline__ void init(const bf16_t* base, long ld, int row0, int tid) {
     rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, 0xffffffff, 0x00020000);
     if constexpr (!KS) {
-      const int row = tid >> 3, ch = tid & 7;
+      // LDS is written linearly (slot = tid); the thread picks the global chunk that
+      // belongs in its slot under the K-contiguous stage layout (see kc_slot below).
+      const int slot = tid >> 3, pos = tid & 7;
+      const int row = kc_slot<TT>(slot);             // the bit swap is its own inverse
+      const int ch = pos ^ ((row / (2 * TT)) & 7);
       voff = (unsigned int)(((long)(row0 + row) * ld + ch * 8) * 2);
+      // chunk `it` of a thread is 32 rows further down; with TT = 4 that flips bit 2 of the
+      // row's swizzle on odd `it`
+      voff_odd = TT == 4 ? (unsigned int)(((long)(row0 + row) * ld + (ch ^ 4) * 8) * 2) : voff;
       it_stride = (unsigned int)(32 * ld * 2);
       k_stride = BK * 2;
-      lds_off = row * 128 + ((ch ^ ((row / TT) & 7)) << 4);
+      lds_off = tid * 16;
     } else {
       const int krow = tid / CPR, ch = tid % CPR;
       voff = (unsigned int)(((long)krow * ld + row0 + ch * 8) * 2);
+      voff_odd = voff;
       it_stride = (unsigned int)((NTHREADS / CPR) * ld * 2);
       k_stride = (unsigned int)(BK * ld * 2);
       lds_off = krow * (R * 2) + ch * 16;
     }
   }
   __device__ __forceinline__ u32x4 load_chunk(int it, int kt) const {
-    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, kt * k_stride + it * it_stride, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (it & 1) ? voff_odd : voff,
+                                                 kt * k_stride + it * it_stride, 0);
   }
   __device__ __forceinline__ void load(u32x4 (&regs)[NCH], int kt) const {
 #pragma unroll
@@ -88,6 +112,9 @@ struct TileLoader {
   // chunks [PART * NCH / 3, (PART + 1) * NCH / 3): a third of the tile per call
   template <int PART>
   __device__ __forceinline__ void store_part(const u32x4 (&regs)[NCH], unsigned char* stage) const {
+#ifdef MLC_PROBE_SKIP_LDS_STORE
+    if (regs[0].x != 0x7fc12345u) return;
+#endif
 #pragma unroll
     for (int it = PART * NCH / 3; it < (PART + 1) * NCH / 3; ++it)
       *reinterpret_cast<u32x4*>(stage + lds_off + it * LDS_IT) = regs[it];
@@ -107,8 +134,16 @@ struct TileLoader {
 //   issue()  : LDS loads into raw registers
 //   finish() : raw registers -> TT fragments of 8 bf16 (a no-op for K-contiguous tiles,
 //              sixteen-bit regrouping for K-strided ones)
-// K-contiguous stage: [R][64] bf16, 16-byte chunks XOR-swizzled by (row / TT) & 7.
+// K-contiguous stage: [R][64] bf16 in the bank-conflict-free slot order of kc_slot.
 // K-strided stage:    [64][R] bf16; a lane reads its TT adjacent rows for each of its 8 k.
+// One v_perm_b32 each: the low (high) 16-bit halves of x and y, x in the low half.
+__device__ __forceinline__ unsigned int pair_lo(unsigned int x, unsigned int y) {
+  return __builtin_amdgcn_perm(y, x, 0x05040100u);
+}
+__device__ __forceinline__ unsigned int pair_hi(unsigned int x, unsigned int y) {
+  return __builtin_amdgcn_perm(y, x, 0x07060302u);
+}
+
 template <int R, int TT, bool KS>
 struct FragReader {
   static constexpr int NRAW = KS ? (TT == 2 ? 8 : 16) : 4 * TT;   // raw dwords
@@ -119,8 +154,8 @@ struct FragReader {
 
   __device__ __forceinline__ void init(int wbase, int l32, int lg) {
     if constexpr (KS) off = lg * 8 * (R * 2) + (wbase + TT * l32) * 2;
-    else off = (wbase + TT * l32) * 128;   // chunk index is applied per slice
-    lane_swz = l32 & 7;
+    else off = (wbase + 2 * TT * (l32 >> 1) + (l32 & 1)) * 128;   // slot of row TT * l32
+    lane_swz = (l32 >> 1) & 7;
     lane_lg = lg;
   }
   int lane_swz, lane_lg;
@@ -142,7 +177,9 @@ struct FragReader {
       const int chunk = ((kk * 2 + lane_lg) ^ lane_swz) << 4;
 #pragma unroll
       for (int t = 0; t < TT; ++t) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + off + t * 128 + chunk);
+        // row TT * l32 + t: bit 0 of t moves up to bit log2(TT) of the slot, bit 1 stays
+        constexpr int SLOT_T[4] = {0, TT, 2, TT + 2};
+        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + off + SLOT_T[t] * 128 + chunk);
         raw[4 * t] = v.x; raw[4 * t + 1] = v.y; raw[4 * t + 2] = v.z; raw[4 * t + 3] = v.w;
       }
     }
@@ -156,39 +193,152 @@ struct FragReader {
     } else if constexpr (TT == 2) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        frag[0][q] = (raw[2 * q] & 0xffffu) | (raw[2 * q + 1] << 16);
-        frag[1][q] = (raw[2 * q] >> 16) | (raw[2 * q + 1] & 0xffff0000u);
+        frag[0][q] = pair_lo(raw[2 * q], raw[2 * q + 1]);
+        frag[1][q] = pair_hi(raw[2 * q], raw[2 * q + 1]);
       }
     } else {
       static_assert(!KS || TT == 2 || TT == 4, "tile interleave is 2 or 4");
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         // raw[2t], raw[2t+1] = the 4 adjacent rows at k = t; pair k = 2q with k = 2q+1
-        frag[0][q] = (raw[4 * q] & 0xffffu) | (raw[4 * q + 2] << 16);
-        frag[1][q] = (raw[4 * q] >> 16) | (raw[4 * q + 2] & 0xffff0000u);
-        frag[2][q] = (raw[4 * q + 1] & 0xffffu) | (raw[4 * q + 3] << 16);
-        frag[3][q] = (raw[4 * q + 1] >> 16) | (raw[4 * q + 3] & 0xffff0000u);
+        frag[0][q] = pair_lo(raw[4 * q], raw[4 * q + 2]);
+        frag[1][q] = pair_hi(raw[4 * q], raw[4 * q + 2]);
+        frag[2][q] = pair_lo(raw[4 * q + 1], raw[4 * q + 3]);
+        frag[3][q] = pair_hi(raw[4 * q + 1], raw[4 * q + 3]);
       }
     }
   }
 };
 
-// Scheduling hint: after each MFMA let the scheduler place the given number of LDS reads,
-// LDS writes, global loads and VALU instructions (masks of sched_group_barrier).
+// Scheduling hint for one k slice (sched_group_barrier masks): the memory instructions
+// (LDS reads and writes, global loads) go between the first MFMAs of the slice, the VALU
+// regrouping of the fragments just read goes between the last ones, by which time the LDS
+// reads it depends on have returned.
 template <int NMFMA, int DSR, int DSW, int VMEM, int VALU>
 __device__ __forceinline__ void interleave_hint() {
+  constexpr int NMEM = VALU > 0 ? NMFMA / 2 : NMFMA;      // MFMAs that carry memory instructions
+  constexpr int NVAL = NMFMA - NMEM;
+  constexpr int r = (DSR + NMEM - 1) / NMEM, w = (DSW + NMEM - 1) / NMEM, v = (VMEM + NMEM - 1) / NMEM;
+  constexpr int a = NVAL > 0 ? (VALU + NVAL - 1) / NVAL : 0;
 #pragma unroll
   for (int i = 0; i < NMFMA; ++i) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    constexpr int r = (DSR + NMFMA - 1) / NMFMA, w = (DSW + NMFMA - 1) / NMFMA,
-                  v = (VMEM + NMFMA - 1) / NMFMA, a = (VALU + NMFMA - 1) / NMFMA;
-    if (r > 0 && i * r < DSR) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
-    if (w > 0 && i * w < DSW) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
-    if (v > 0 && i * v < VMEM) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
-    if (a > 0 && i * a < VALU) __builtin_amdgcn_sched_group_barrier(0x002, a, 0);
+    if (i < NMEM) {
+      if (r > 0 && i * r < DSR) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+      if (w > 0 && i * w < DSW) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+      if (v > 0 && i * v < VMEM) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+    } else {
+      if (a > 0 && (i - NMEM) * a < VALU) __builtin_amdgcn_sched_group_barrier(0x002, a, 0);
+    }
   }
 }
 
+// Position of an output tile.
+struct TileCoord { int b, m0, n0; bool mirror; };
+
+// Epilogue of one tile: D = alpha_b * acc + beta * C + gamma * I, stored as bf16.  With
+// tc.mirror the transposed tile is stored as well (symmetric outputs compute only the lower
+// triangle of tiles).  HAS_C is compile-time so that the C loads can be issued back to back.
+template <int TM, int TN, bool HAS_C>
+__device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc)[TM][TN],
+                                           const TileCoord& tc, float alpha, bool on_diag,
+                                           int wbase_m, int wbase_n, int l32, int lg) {
+  // Lane owns TN adjacent columns; accumulator register r of tile i is row
+  // TM * (8 * (r / 4) + 4 * lg + r % 4) + i of the wavefront's block: for a fixed r / 4 that
+  // is 4 * TM consecutive rows.  All accesses go through buffer resources on the batch's
+  // matrix: one lane offset in a VGPR, the row offset in a scalar register.
+  const int col0 = tc.n0 + wbase_n + TN * l32;
+  const int row_lane = tc.m0 + wbase_m + TM * 4 * lg;
+  const __amdgpu_buffer_rsrc_t rd =
+      __builtin_amdgcn_make_buffer_rsrc(g.D + (long)tc.b * g.strideD, 0, 0xffffffff, 0x00020000);
+  const unsigned int ldd2 = (unsigned int)(g.ldd * 2), ldc2 = (unsigned int)(g.ldc * 2);
+  const unsigned int voff_d = (unsigned int)(((long)row_lane * g.ldd + col0) * 2);
+  const unsigned int voff_m = (unsigned int)(((long)col0 * g.ldd + row_lane) * 2);   // transposed
+  const unsigned int voff_c = HAS_C ? (unsigned int)(((long)row_lane * g.ldc + col0) * 2) : 0u;
+  __amdgpu_buffer_rsrc_t rc = rd;
+  if constexpr (HAS_C)
+    rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(g.C) + (long)tc.b * g.strideC, 0,
+                                           0xffffffff, 0x00020000);
+  const int diag = col0 - row_lane;     // row offset (within the lane's rows) that meets column col0
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    unsigned int packed[4][TM][TN / 2];                   // [r % 4][i][column pair]
+    u32x2 cval[4][TM];
+    if constexpr (HAS_C) {
+#pragma unroll
+      for (int rl = 0; rl < 4; ++rl)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const unsigned int soff = (unsigned int)(TM * (8 * q + rl) + i) * ldc2;
+          if constexpr (TN == 2) cval[rl][i].x = __builtin_amdgcn_raw_buffer_load_b32(rc, voff_c, soff, 0);
+          else cval[rl][i] = __builtin_amdgcn_raw_buffer_load_b64(rc, voff_c, soff, 0);
+        }
+    }
+#pragma unroll
+    for (int rl = 0; rl < 4; ++rl) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = 4 * q + rl;
+        const int roff = TM * (8 * q + rl) + i;           // compile-time row offset
+        float v[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) v[j] = alpha * acc[i][j][r];
+        if constexpr (HAS_C) {
+          v[0] += g.beta * bf16lo(cval[rl][i].x);
+          v[1] += g.beta * bf16hi(cval[rl][i].x);
+          if constexpr (TN == 4) {
+            v[2] += g.beta * bf16lo(cval[rl][i].y);
+            v[3] += g.beta * bf16hi(cval[rl][i].y);
+          }
+        }
+        if (on_diag) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            if (roff == diag + j) v[j] += g.gamma;
+        }
+        packed[rl][i][0] = pack_bf16x2(v[0], v[1]);
+        if constexpr (TN == 4) packed[rl][i][1] = pack_bf16x2(v[2], v[3]);
+        const unsigned int soff = (unsigned int)roff * ldd2;
+        if constexpr (TN == 2) {
+          __builtin_amdgcn_raw_buffer_store_b32(packed[rl][i][0], rd, voff_d, soff, 0);
+        } else {
+          u32x2 w;
+          w.x = packed[rl][i][0];
+          w.y = packed[rl][i][1];
+          __builtin_amdgcn_raw_buffer_store_b64(w, rd, voff_d, soff, 0);
+        }
+      }
+    }
+    if (tc.mirror) {
+      // Column col0 + j of this tile becomes a row of the mirrored tile; the lane's 4 * TM
+      // consecutive rows (order: r % 4 major, i minor) become 4 * TM adjacent elements.
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        unsigned int w[2 * TM];
+#pragma unroll
+        for (int e = 0; e < 4 * TM; e += 2) {
+          // elements e and e + 1: (rl, i) = (e / TM, e % TM) and the next i
+          const unsigned int lo = packed[e / TM][e % TM][j / 2];
+          const unsigned int hi = packed[(e + 1) / TM][(e + 1) % TM][j / 2];
+          w[e / 2] = (j & 1) ? pair_hi(lo, hi) : pair_lo(lo, hi);
+        }
+        const unsigned int soff = (unsigned int)j * ldd2 + (unsigned int)(TM * 8 * q) * 2;
+#pragma unroll
+        for (int x = 0; x < 2 * TM; x += 4) {
+          u32x4 ww;
+          ww.x = w[x]; ww.y = w[x + 1]; ww.z = w[x + 2]; ww.w = w[x + 3];
+          __builtin_amdgcn_raw_buffer_store_b128(ww, rd, voff_m, soff + x * 4, 0);
+        }
+      }
+    }
+  }
+}
+
+// Persistent kernel: one workgroup per CU slot walks over its share of the output tiles.
+// Workgroups are dealt round-robin to the 8 XCDs, so XCD x owns the contiguous range of
+// tiles [x * tiles_per_xcd, (x + 1) * tiles_per_xcd) and its workgroups take them in
+// order: tiles that share operand panels run at the same time behind the same L2.  The
+// first global loads of the next tile are issued before the epilogue of the current one.
 template <int BM, int BN, bool AKS, bool BKS>
 __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -197,20 +347,30 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   auto sA = [&](int buf) { return smem + buf * A_BYTES; };
   auto sB = [&](int buf) { return smem + 2 * A_BYTES + buf * B_BYTES; };
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
-  // tiles so that the tiles sharing operand panels also share that XCD's L2.
-  const int bid = blockIdx.x;
-#ifdef MLC_PROBE_NO_XCD_REMAP
-  const int logical = bid;
-#else
-  const int logical = (bid % NUM_XCD) * g.tiles_per_xcd + bid / NUM_XCD;
-#endif
-  if (logical >= g.total_tiles) return;
-  const int per_mat = g.tiles_m * g.tiles_n;
-  const int b = logical / per_mat;
-  const int rem = logical - b * per_mat;
-  const int tile_m = rem / g.tiles_n, tile_n = rem - tile_m * g.tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
+  const int range_end = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
+  int logical = xcd * g.tiles_per_xcd + slot;
+  if (logical >= range_end) return;
+
+  auto decode = [&](int t) {
+    TileCoord tc;
+    tc.b = t / g.tiles_per_mat;
+    const int rem = t - tc.b * g.tiles_per_mat;
+    int tm, tn;
+    if (g.symmetric) {          // lower triangle, row-major: rem = tm (tm + 1) / 2 + tn
+      tm = (int)((sqrtf(8.f * (float)rem + 1.f) - 1.f) * 0.5f);
+      while ((tm + 1) * (tm + 2) / 2 <= rem) ++tm;
+      while (tm * (tm + 1) / 2 > rem) --tm;
+      tn = rem - tm * (tm + 1) / 2;
+    } else {
+      tm = rem / g.tiles_n;
+      tn = rem - tm * g.tiles_n;
+    }
+    tc.m0 = tm * BM;
+    tc.n0 = tn * BN;
+    tc.mirror = g.symmetric && tm != tn;
+    return tc;
+  };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -218,28 +378,12 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
   const int wbase_m = wm * (BM / 2), wbase_n = wn * (BN / 2);
 
-  TileLoader<BM, AKS> ldA;
-  TileLoader<BN, BKS> ldB;
-#ifdef MLC_PROBE_SAME_TILE
-  ldA.template init<TM>(g.A, g.lda, 0, tid);
-  ldB.template init<TN>(g.B, g.ldb, 0, tid);
-#else
-  ldA.template init<TM>(g.A + (long)b * g.strideA, g.lda, m0, tid);
-  ldB.template init<TN>(g.B + (long)b * g.strideB, g.ldb, n0, tid);
-#endif
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
   using LoaderA = TileLoader<BM, AKS>;
   using LoaderB = TileLoader<BN, BKS>;
   using ReaderA = FragReader<BM, TM, AKS>;
   using ReaderB = FragReader<BN, TN, BKS>;
+  LoaderA ldA;
+  LoaderB ldB;
   // Two sets of staging registers: while one set's tile is being written to LDS, the
   // other set's global loads (two tiles ahead) are still in flight.
   u32x4 ra[2][LoaderA::NCH], rb[2][LoaderB::NCH];
@@ -248,28 +392,15 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   rdA.init(wbase_m, l32, lg);
   rdB.init(wbase_n, l32, lg);
   u32x4 fa[2][TM], fb[2][TN];
+  f32x16 acc[TM][TN];
   const int KT = g.K / BK;      // even: K is a multiple of 128
 
-  // Software pipeline over 16-deep k slices.  While the MFMAs of slice kk run, the LDS
-  // reads of slice kk+1 are in flight; slices 0-2 also move a third of tile kt+1 from its
-  // staging set to the other LDS stage, and slices 1-3 issue the global loads of tile kt+3
-  // into the registers just freed (spread out so that the 64 B/clk vector-memory path
-  // never has to absorb a whole tile at once).  One barrier per 64-deep step, after slice 2.
-  ldA.load(ra[0], 0);
-  ldB.load(rb[0], 0);
-  ldA.load(ra[1], 1);
-  ldB.load(rb[1], 1);
-  ldA.store(ra[0], sA(0));
-  ldB.store(rb[0], sB(0));
-  if (KT > 2) {
-    ldA.load(ra[0], 2);
-    ldB.load(rb[0], 2);
-  }
-  __syncthreads();
-  rdA.issue(sA(0), 0);
-  rdB.issue(sB(0), 0);
-  rdA.finish(fa[0]);
-  rdB.finish(fb[0]);
+  auto start_tile = [&](const TileCoord& tc) {   // loader state + the first K tile
+    ldA.template init<TM>(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
+    ldB.template init<TN>(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
+    ldA.load(ra[0], 0);
+    ldB.load(rb[0], 0);
+  };
 
   auto mfma_slice = [&](int buf) {
 #pragma unroll
@@ -284,8 +415,14 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   constexpr int NDSR = ReaderA::NLOADS + ReaderB::NLOADS;
   constexpr int NPERM = ReaderA::NPERM + ReaderB::NPERM;
 
-  // One 64-deep step on stage kt & 1.  SET: staging set that holds tile kt+1 (= (kt+1) & 1).
-  // STORE: tile kt+1 exists and goes to the other stage.  LOAD: tile kt+3 exists.
+  // One 64-deep step on stage kt & 1, software-pipelined over its four 16-deep k slices.
+  // While the MFMAs of slice kk run, the LDS reads of slice kk+1 are in flight; slices 0-2
+  // also move a third of tile kt+1 from its staging set to the other LDS stage, and slices
+  // 1-3 issue the global loads of tile kt+3 into the registers just freed (spread out so
+  // that the 64 B/clk vector-memory path never has to absorb a whole tile at once).  One
+  // barrier per step, after slice 2.
+  // SET: staging set that holds tile kt+1 (= (kt+1) & 1).  STORE: tile kt+1 exists and goes
+  // to the other stage.  LOAD: tile kt+3 exists.
   auto kstep = [&](int kt, auto set_tag, auto store_tag, auto load_tag) {
     constexpr int SET = decltype(set_tag)::value;
     constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
@@ -304,27 +441,21 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
     // slice 1
     rdA.issue(a_cur, 2); rdB.issue(b_cur, 2);
     if constexpr (STORE) { ldA.template store_part<1>(ra[SET], a_nxt); ldB.template store_part<1>(rb[SET], b_nxt); }
-#ifndef MLC_PROBE_SKIP_GLOBAL
     if constexpr (LOAD) { ldA.template load_part<0>(ra[SET], kt + 3); ldB.template load_part<0>(rb[SET], kt + 3); }
-#endif
     mfma_slice(1);
     rdA.finish(fa[0]); rdB.finish(fb[0]);
     interleave_hint<NM, NDSR, STORE ? P1 : 0, LOAD ? P0 : 0, NPERM>();
     // slice 2
     rdA.issue(a_cur, 3); rdB.issue(b_cur, 3);
     if constexpr (STORE) { ldA.template store_part<2>(ra[SET], a_nxt); ldB.template store_part<2>(rb[SET], b_nxt); }
-#ifndef MLC_PROBE_SKIP_GLOBAL
     if constexpr (LOAD) { ldA.template load_part<1>(ra[SET], kt + 3); ldB.template load_part<1>(rb[SET], kt + 3); }
-#endif
     mfma_slice(0);
     rdA.finish(fa[1]); rdB.finish(fb[1]);
     interleave_hint<NM, NDSR, STORE ? P2 : 0, LOAD ? P1 : 0, NPERM>();
     if constexpr (STORE) __syncthreads();
     // slice 3
     if constexpr (STORE) { rdA.issue(a_nxt, 0); rdB.issue(b_nxt, 0); }
-#ifndef MLC_PROBE_SKIP_GLOBAL
     if constexpr (LOAD) { ldA.template load_part<2>(ra[SET], kt + 3); ldB.template load_part<2>(rb[SET], kt + 3); }
-#endif
     mfma_slice(1);
     if constexpr (STORE) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
     interleave_hint<NM, STORE ? NDSR : 0, 0, LOAD ? P2 : 0, STORE ? NPERM : 0>();
@@ -333,75 +464,79 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   using F = std::false_type;
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
-  int kt = 0;
-  for (; kt + 4 < KT; kt += 2) {
-    kstep(kt, S1{}, T{}, T{});
-    kstep(kt + 1, S0{}, T{}, T{});
-  }
-  if (kt + 4 == KT) {            // four steps left: only the first still has a tile to fetch
-    kstep(kt, S1{}, T{}, T{});
-    kstep(kt + 1, S0{}, T{}, F{});
-    kt += 2;
-  }
-  kstep(kt, S1{}, T{}, F{});     // two steps left
-  kstep(kt + 1, S0{}, F{}, F{});
 
-  // ---- epilogue: D = alpha_b * acc + beta * C + gamma * I ---------------------------
-  float alpha = g.alpha;
-#ifdef MLC_PROBE_SKIP_EPILOGUE
-  if (alpha != 12345.f) return;
-#endif
-  if (g.bscale) {
-    const float s = g.bscale[b];
-    alpha *= (g.bscale_pow == 2) ? s * s : s;
-  }
-  // Lane owns TN adjacent columns; accumulator register r of tile i is row
-  // TM * (8 * (r / 4) + 4 * lg + r % 4) + i of the wavefront's block.
-  const int col0 = n0 + wbase_n + TN * l32;
-  const int row_lane = m0 + wbase_m + TM * 4 * lg;
-  bf16_t* dlane = g.D + (long)b * g.strideD + (long)row_lane * g.ldd + col0;
-  const bf16_t* clane = g.C ? g.C + (long)b * g.strideC + (long)row_lane * g.ldc + col0 : nullptr;
-  // the diagonal crosses this workgroup's tile only if the row and column ranges overlap
-  const bool on_diag = g.gamma != 0.f && m0 < n0 + BN && n0 < m0 + BM;
-  const int diag = col0 - row_lane;     // row offset (within the lane's rows) that meets column col0
+  TileCoord tc = decode(logical);
+  start_tile(tc);
+  while (true) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int roff = TM * (8 * (r >> 2) + (r & 3)) + i;    // compile-time row offset
-      float v[TN];
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) v[j] = alpha * acc[i][j][r];
-      if (clane) {
-        const bf16_t* c = clane + (long)roff * g.ldc;
-        if constexpr (TN == 2) {
-          const unsigned int w = *reinterpret_cast<const unsigned int*>(c);
-          v[0] += g.beta * bf16lo(w);
-          v[1] += g.beta * bf16hi(w);
-        } else {
-          const u32x2 w = *reinterpret_cast<const u32x2*>(c);
-          v[0] += g.beta * bf16lo(w.x);
-          v[1] += g.beta * bf16hi(w.x);
-          v[2] += g.beta * bf16lo(w.y);
-          v[3] += g.beta * bf16hi(w.y);
-        }
-      }
-      if (on_diag) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          if (roff == diag + j) v[j] += g.gamma;
-      }
-      bf16_t* d = dlane + (long)roff * g.ldd;
-      if constexpr (TN == 2) {
-        *reinterpret_cast<unsigned int*>(d) = pack_bf16x2(v[0], v[1]);
-      } else {
-        u32x2 w;
-        w.x = pack_bf16x2(v[0], v[1]);
-        w.y = pack_bf16x2(v[2], v[3]);
-        *reinterpret_cast<u32x2*>(d) = w;
-      }
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // K tile 1 -> set 1; K tile 0 -> LDS stage 0 (every wave has left the previous tile's
+    // step KT-2, the last one that read stage 0, through that step's barrier); K tile 2 ->
+    // set 0.
+    ldA.load(ra[1], 1);
+    ldB.load(rb[1], 1);
+    ldA.store(ra[0], sA(0));
+    ldB.store(rb[0], sB(0));
+    if (KT > 2) {
+      ldA.load(ra[0], 2);
+      ldB.load(rb[0], 2);
     }
+    __syncthreads();
+    rdA.issue(sA(0), 0);
+    rdB.issue(sB(0), 0);
+    rdA.finish(fa[0]);
+    rdB.finish(fb[0]);
+
+    int kt = 0;
+    for (; kt + 4 < KT; kt += 2) {
+      kstep(kt, S1{}, T{}, T{});
+      kstep(kt + 1, S0{}, T{}, T{});
+    }
+    if (kt + 4 == KT) {            // four steps left: only the first still has a tile to fetch
+      kstep(kt, S1{}, T{}, T{});
+      kstep(kt + 1, S0{}, T{}, F{});
+      kt += 2;
+    }
+    kstep(kt, S1{}, T{}, F{});     // two steps left
+    kstep(kt + 1, S0{}, F{}, F{});
+
+    const int next = logical + g.wg_per_xcd;
+    const bool more = next < range_end;
+    float alpha = g.alpha;
+    if (g.bscale) {
+      const float sc = g.bscale[tc.b];
+      alpha *= (g.bscale_pow == 2) ? sc * sc : sc;
+    }
+    // the diagonal crosses this tile only if its row and column ranges overlap
+    const bool on_diag = g.gamma != 0.f && tc.m0 < tc.n0 + BN && tc.n0 < tc.m0 + BM;
+#ifdef MLC_PROBE_SKIP_EPILOGUE
+    if (alpha == 12345.f)
+#endif
+    {
+      if (g.C) store_tile<TM, TN, true>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
+      else store_tile<TM, TN, false>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
+    }
+    if (!more) break;
+    logical = next;
+    tc = decode(logical);
+    start_tile(tc);
   }
+}
+
+int cus_per_xcd() {
+  static int cached = 0;
+  if (cached == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || cus < NUM_XCD)
+      cus = 256;
+    cached = cus / NUM_XCD;
+  }
+  return cached;
 }
 
 template <int BM, int BN, bool AKS, bool BKS>
@@ -413,10 +548,21 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   g.C = d.C; g.ldc = d.ldc; g.strideC = d.strideC;
   g.K = d.K; g.batch = d.batch;
   g.tiles_m = d.M / BM; g.tiles_n = d.N / BN;
-  const long total = (long)g.tiles_m * g.tiles_n * d.batch;
+  g.symmetric = d.symmetric ? 1 : 0;
+  if (g.symmetric && (BM != BN || d.M != d.N)) return MLC_ERR_SHAPE;
+  g.tiles_per_mat = g.symmetric ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
+  const long total = (long)g.tiles_per_mat * d.batch;
   if (total <= 0 || total > (1L << 30)) return MLC_ERR_SHAPE;
   g.total_tiles = (int)total;
   g.tiles_per_xcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
+  // one workgroup per CU for the 256 x 256 tile (128 KiB of LDS each), two for 128 x 128
+  const int per_cu = (BM == 256) ? 1 : 2;
+#ifdef MLC_PROBE_NONPERSISTENT
+  g.wg_per_xcd = g.tiles_per_xcd; (void)per_cu;
+#else
+  g.wg_per_xcd = cus_per_xcd() * per_cu;
+#endif
+  if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
   g.alpha = d.alpha; g.beta = d.beta; g.gamma = d.gamma;
   g.bscale = d.bscale; g.bscale_pow = d.bscale_pow;
   const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
@@ -428,16 +574,17 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
       return MLC_ERR_LAUNCH;
     attr_set = true;
   }
-  const double flops = 2.0 * d.M * d.N * (double)d.K * d.batch;
+  const double flops = 2.0 * BM * BN * (double)d.K * (double)total;   // executed, not nominal
   LaunchScope scope(MLC_KERNEL_NS_GEMM, stream, flops, 0.0);
-  hipLaunchKernelGGL(kern, dim3(g.tiles_per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, g);
+  hipLaunchKernelGGL(kern, dim3(g.wg_per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, g);
   return hipGetLastError() == hipSuccess ? MLC_OK : MLC_ERR_LAUNCH;
 }
 
 template <int BM, int BN>
 int launch_layout(const GemmDesc& d, hipStream_t stream) {
+  // Newton-Schulz needs only these two: a symmetric operand can be read either way, so the
+  // mixed cases never arise.
   if (!d.a_kstrided && !d.b_kstrided) return launch_cfg<BM, BN, false, false>(d, stream);
-  if (!d.a_kstrided && d.b_kstrided) return launch_cfg<BM, BN, false, true>(d, stream);
   if (d.a_kstrided && d.b_kstrided) return launch_cfg<BM, BN, true, true>(d, stream);
   return MLC_ERR_UNSUPPORTED;
 }
