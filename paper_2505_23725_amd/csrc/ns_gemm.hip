@@ -3,8 +3,14 @@
 //
 // One workgroup = 256 threads = 4 wavefronts in a 2 x 2 arrangement; each wavefront owns a
 // (BM/2) x (BN/2) block of the output tile as TM x TN accumulators of v_mfma_f32_32x32x16_bf16.
-// Tiles of both operands are staged through LDS (double buffered, one barrier per 64-deep
-// K step) from registers that were filled by the previous step's global loads.
+//
+// Operand tiles travel HBM -> LDS directly (buffer_load ... lds): no staging registers, no
+// LDS store instructions.  The LDS holds a ring of four 32-deep stages; a stage is refilled
+// as soon as every wavefront has read it, three stages (96 k) ahead of its use, and all four
+// stages of the next output tile are requested before the current tile's epilogue.  The
+// compiler does not model these transfers, so their completion is awaited explicitly
+// (s_waitcnt vmcnt(n): a wavefront's vector-memory loads complete in issue order) before the
+// barrier that publishes a stage.
 //
 // An operand whose K index is the slow one in memory ("K-strided": X in B'X for wide
 // matrices, both operands of X^T X for tall ones) is never transposed in HBM.  Its tile is
@@ -23,10 +29,14 @@ namespace mlc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+template <int V> using I = std::integral_constant<int, V>;
 
 namespace {
 
-constexpr int BK = 64;           // K depth of one LDS stage
+constexpr int BK = 32;           // K depth of one LDS stage
+constexpr int NSTAGE = 4;        // stages in the LDS ring
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 
@@ -42,89 +52,79 @@ struct GemmArgs {
   const float* bscale; int bscale_pow;
 };
 
-// K-contiguous stage layout: [R row slots][8 chunks of 16 B].  The LDS has 64 four-byte
-// banks and serves a 128-bit read 16 lanes at a time, so the 16 chunks read by lanes
-// 0-15 (same k chunk, rows TT apart) must land on 16 different 16-byte columns of the
-// 256-byte bank line.  Row r therefore lives in slot kc_slot(r) = r with bit 0 and bit
-// log2(TT) exchanged (rows TT apart alternate between the two 128-byte halves), and chunk c
-// of row r sits at position c ^ ((r / (2 TT)) & 7) inside the slot.
+// ---- K-contiguous stage layout ------------------------------------------------------
+// [R row slots][4 chunks of 16 B].  The LDS has 64 four-byte banks and serves a 128-bit read
+// 16 lanes at a time, so the 16 chunks read by lanes 0-15 (same k chunk, rows TT apart) must
+// land on 16 different 16-byte columns of the 256-byte bank line, i.e. on 4 different slots
+// mod 4 times 4 different chunk positions.  Row TT*l + t (l = lane % 32) lives in slot
+// 4*TT*(l/4) + 4*t + l%4, and chunk c of that row sits at position c ^ ((l/4) & 3).
 template <int TT>
-__device__ __forceinline__ int kc_slot(int row) {
-  constexpr int HB = TT == 4 ? 2 : 1;             // log2(TT)
-  const int b0 = row & 1, bh = (row >> HB) & 1;
-  return (row & ~(1 | (1 << HB))) | (b0 << HB) | bh;
+__device__ __forceinline__ int kc_slot_to_row(int slot) {     // inverse of the map above
+  const int l_lo = slot & 3, t = (slot >> 2) & (TT - 1), hi = slot / (4 * TT);
+  return TT * (4 * hi + l_lo) + t;
+}
+template <int TT>
+__device__ __forceinline__ int kc_swizzle(int row) { return (row / (4 * TT)) & 3; }
+
+// Raw buffer resource (base, no stride, unbounded, dword data format) for a matrix.
+__device__ __forceinline__ i32x4 make_rsrc(const void* p) {
+  const unsigned long a = (unsigned long)p;
+  i32x4 r;
+  r.x = __builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
+  r.y = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
+  r.z = -1;
+  r.w = 0x00020000;
+  return r;
 }
 
-// ---- global -> register staging of one operand tile (R rows x 64 k) -----------------
-// Loads go through a raw buffer resource on the matrix (base in SGPRs, one 32-bit lane
-// offset in a VGPR, everything that changes per chunk or per K step in a scalar offset),
-// so the loader costs one address VGPR instead of a 64-bit pointer per chunk.
-template <int R, bool KS>
-struct TileLoader {
-  static constexpr int NCH = R / 32;            // 16-byte chunks per thread
-  static constexpr int CPR = R / 8;             // chunks per k-row when K-strided
-  __amdgpu_buffer_rsrc_t rsrc;                  // the matrix (at most 4 GiB)
-  unsigned int voff;                            // lane's byte offset of its first chunk, k = 0
-  unsigned int voff_odd;                        // same for odd chunk indices (K-contiguous, TT = 4)
-  unsigned int it_stride;                       // bytes between a thread's chunks
-  unsigned int k_stride;                        // bytes per K step
-  int lds_off;                                  // byte offset of the first chunk in the stage
-  static constexpr int LDS_IT = 4096;           // bytes between a thread's chunks in LDS
+// 16 bytes per lane from rsrc[voff + soff] straight into LDS at lds_off + 16 * lane
+// (lds_off is wavefront-uniform and relative to the workgroup's LDS allocation).
+__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\t"
+               "s_nop 0\n\t"
+               "buffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
 
-  template <int TT>
+// ---- HBM -> LDS transfer of one operand's stage (R rows x 32 k) -----------------------
+// Chunk c = it * 256 + tid of a stage lands at LDS byte c * 16, so a wavefront's 64 lanes
+// fill 1 KiB contiguously; which global chunk a lane fetches follows from the stage layout.
+template <int R, int TT, bool KS>
+struct StageLoader {
+  static constexpr int NCH = R / 64;            // transfers per thread per stage
+  static constexpr int CPR = R / 8;             // chunks per k-row when K-strided
+  i32x4 rsrc;
+  unsigned int voff;                            // lane's byte offset of its first chunk, k = 0
+  unsigned int it_stride;                       // bytes between a thread's chunks
+  unsigned int k_stride;                        // bytes per stage
+  unsigned int wave_lds;                        // wave * 1024
+
   __device__ __forceinline__ void init(const bf16_t* base, long ld, int row0, int tid) {
-    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, 0xffffffff, 0x00020000);
+    rsrc = make_rsrc(base);
+    wave_lds = (unsigned int)__builtin_amdgcn_readfirstlane((tid >> 6) * 1024);
     if constexpr (!KS) {
-      // LDS is written linearly (slot = tid); the thread picks the global chunk that
-      // belongs in its slot under the K-contiguous stage layout (see kc_slot below).
-      const int slot = tid >> 3, pos = tid & 7;
-      const int row = kc_slot<TT>(slot);             // the bit swap is its own inverse
-      const int ch = pos ^ ((row / (2 * TT)) & 7);
+      const int slot = tid >> 2, pos = tid & 3;
+      const int row = kc_slot_to_row<TT>(slot);
+      const int ch = pos ^ kc_swizzle<TT>(row);
       voff = (unsigned int)(((long)(row0 + row) * ld + ch * 8) * 2);
-      // chunk `it` of a thread is 32 rows further down; with TT = 4 that flips bit 2 of the
-      // row's swizzle on odd `it`
-      voff_odd = TT == 4 ? (unsigned int)(((long)(row0 + row) * ld + (ch ^ 4) * 8) * 2) : voff;
-      it_stride = (unsigned int)(32 * ld * 2);
+      it_stride = (unsigned int)(64 * ld * 2);      // 64 slots = 64 rows further down
       k_stride = BK * 2;
-      lds_off = tid * 16;
     } else {
       const int krow = tid / CPR, ch = tid % CPR;
       voff = (unsigned int)(((long)krow * ld + row0 + ch * 8) * 2);
-      voff_odd = voff;
       it_stride = (unsigned int)((NTHREADS / CPR) * ld * 2);
       k_stride = (unsigned int)(BK * ld * 2);
-      lds_off = krow * (R * 2) + ch * 16;
     }
   }
-  __device__ __forceinline__ u32x4 load_chunk(int it, int kt) const {
-    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (it & 1) ? voff_odd : voff,
-                                                 kt * k_stride + it * it_stride, 0);
-  }
-  __device__ __forceinline__ void load(u32x4 (&regs)[NCH], int kt) const {
-#pragma unroll
-    for (int it = 0; it < NCH; ++it) regs[it] = load_chunk(it, kt);
-  }
-  __device__ __forceinline__ void store(const u32x4 (&regs)[NCH], unsigned char* stage) const {
+  // all NCH transfers of K tile kt into the stage at LDS byte offset `stage`
+  __device__ __forceinline__ void issue(int kt, unsigned int stage) const {
 #pragma unroll
     for (int it = 0; it < NCH; ++it)
-      *reinterpret_cast<u32x4*>(stage + lds_off + it * LDS_IT) = regs[it];
-  }
-  // chunks [PART * NCH / 3, (PART + 1) * NCH / 3): a third of the tile per call
-  template <int PART>
-  __device__ __forceinline__ void store_part(const u32x4 (&regs)[NCH], unsigned char* stage) const {
-#ifdef MLC_PROBE_SKIP_LDS_STORE
-    if (regs[0].x != 0x7fc12345u) return;
-#endif
-#pragma unroll
-    for (int it = PART * NCH / 3; it < (PART + 1) * NCH / 3; ++it)
-      *reinterpret_cast<u32x4*>(stage + lds_off + it * LDS_IT) = regs[it];
-  }
-  template <int PART>
-  static constexpr int part_count() { return (PART + 1) * NCH / 3 - PART * NCH / 3; }
-  template <int PART>
-  __device__ __forceinline__ void load_part(u32x4 (&regs)[NCH], int kt) const {
-#pragma unroll
-    for (int it = PART * NCH / 3; it < (PART + 1) * NCH / 3; ++it) regs[it] = load_chunk(it, kt);
+      dma16(rsrc, voff, kt * k_stride + it * it_stride, stage + it * 4096 + wave_lds);
   }
 };
 
@@ -134,8 +134,7 @@ struct TileLoader {
 //   issue()  : LDS loads into raw registers
 //   finish() : raw registers -> TT fragments of 8 bf16 (a no-op for K-contiguous tiles,
 //              sixteen-bit regrouping for K-strided ones)
-// K-contiguous stage: [R][64] bf16 in the bank-conflict-free slot order of kc_slot.
-// K-strided stage:    [64][R] bf16; a lane reads its TT adjacent rows for each of its 8 k.
+// K-strided stage: [32][R] bf16; a lane reads its TT adjacent rows for each of its 8 k.
 // One v_perm_b32 each: the low (high) 16-bit halves of x and y, x in the low half.
 __device__ __forceinline__ unsigned int pair_lo(unsigned int x, unsigned int y) {
   return __builtin_amdgcn_perm(y, x, 0x05040100u);
@@ -151,15 +150,14 @@ struct FragReader {
   static constexpr int NPERM = KS ? 4 * TT : 0;                   // regrouping instructions
   unsigned int raw[NRAW];
   int off;     // lane's byte offset inside a stage for k slice 0
+  int lane_swz, lane_lg;
 
   __device__ __forceinline__ void init(int wbase, int l32, int lg) {
     if constexpr (KS) off = lg * 8 * (R * 2) + (wbase + TT * l32) * 2;
-    else off = (wbase + 2 * TT * (l32 >> 1) + (l32 & 1)) * 128;   // slot of row TT * l32
-    lane_swz = (l32 >> 1) & 7;
+    else off = (wbase + 4 * TT * (l32 >> 2) + (l32 & 3)) * 64;     // slot of row TT * l32
+    lane_swz = (l32 >> 2) & 3;
     lane_lg = lg;
   }
-  int lane_swz, lane_lg;
-
   __device__ __forceinline__ void issue(const unsigned char* stage, int kk) {
     if constexpr (KS) {
       const unsigned char* p = stage + off + kk * 16 * (R * 2);
@@ -176,10 +174,8 @@ struct FragReader {
     } else {
       const int chunk = ((kk * 2 + lane_lg) ^ lane_swz) << 4;
 #pragma unroll
-      for (int t = 0; t < TT; ++t) {
-        // row TT * l32 + t: bit 0 of t moves up to bit log2(TT) of the slot, bit 1 stays
-        constexpr int SLOT_T[4] = {0, TT, 2, TT + 2};
-        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + off + SLOT_T[t] * 128 + chunk);
+      for (int t = 0; t < TT; ++t) {               // row TT * l32 + t is 4 slots (256 B) per t
+        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + off + t * 256 + chunk);
         raw[4 * t] = v.x; raw[4 * t + 1] = v.y; raw[4 * t + 2] = v.z; raw[4 * t + 3] = v.w;
       }
     }
@@ -210,23 +206,20 @@ struct FragReader {
   }
 };
 
-// Scheduling hint for one k slice (sched_group_barrier masks): the memory instructions
-// (LDS reads and writes, global loads) go between the first MFMAs of the slice, the VALU
-// regrouping of the fragments just read goes between the last ones, by which time the LDS
-// reads it depends on have returned.
-template <int NMFMA, int DSR, int DSW, int VMEM, int VALU>
+// Scheduling hint for one k slice (sched_group_barrier masks): LDS reads go between the
+// first MFMAs of the slice, the VALU regrouping of the fragments just read goes between the
+// last ones, by which time the LDS reads it depends on have returned.
+template <int NMFMA, int DSR, int VALU>
 __device__ __forceinline__ void interleave_hint() {
-  constexpr int NMEM = VALU > 0 ? NMFMA / 2 : NMFMA;      // MFMAs that carry memory instructions
+  constexpr int NMEM = VALU > 0 ? NMFMA / 2 : NMFMA;
   constexpr int NVAL = NMFMA - NMEM;
-  constexpr int r = (DSR + NMEM - 1) / NMEM, w = (DSW + NMEM - 1) / NMEM, v = (VMEM + NMEM - 1) / NMEM;
+  constexpr int r = (DSR + NMEM - 1) / NMEM;
   constexpr int a = NVAL > 0 ? (VALU + NVAL - 1) / NVAL : 0;
 #pragma unroll
   for (int i = 0; i < NMFMA; ++i) {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     if (i < NMEM) {
       if (r > 0 && i * r < DSR) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
-      if (w > 0 && i * w < DSW) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
-      if (v > 0 && i * v < VMEM) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
     } else {
       if (a > 0 && (i - NMEM) * a < VALU) __builtin_amdgcn_sched_group_barrier(0x002, a, 0);
     }
@@ -262,6 +255,9 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
   const int diag = col0 - row_lane;     // row offset (within the lane's rows) that meets column col0
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
+    // keep the scheduler from pulling the next quarter's accumulator reads up here: all 256
+    // accumulators in VGPRs at once do not fit
+    __builtin_amdgcn_sched_barrier(0);
     unsigned int packed[4][TM][TN / 2];                   // [r % 4][i][column pair]
     u32x2 cval[4][TM];
     if constexpr (HAS_C) {
@@ -337,15 +333,16 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
 // Persistent kernel: one workgroup per CU slot walks over its share of the output tiles.
 // Workgroups are dealt round-robin to the 8 XCDs, so XCD x owns the contiguous range of
 // tiles [x * tiles_per_xcd, (x + 1) * tiles_per_xcd) and its workgroups take them in
-// order: tiles that share operand panels run at the same time behind the same L2.  The
-// first global loads of the next tile are issued before the epilogue of the current one.
+// order: tiles that share operand panels run at the same time behind the same L2.
 template <int BM, int BN, bool AKS, bool BKS>
 __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  auto sA = [&](int buf) { return smem + buf * A_BYTES; };
-  auto sB = [&](int buf) { return smem + 2 * A_BYTES + buf * B_BYTES; };
+  const unsigned int lds0 =
+      (unsigned int)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem;
+  auto sA = [&](int st) { return smem + st * STAGE_BYTES; };
+  auto sB = [&](int st) { return smem + st * STAGE_BYTES + A_BYTES; };
 
   const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
   const int range_end = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
@@ -378,28 +375,30 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
   const int wbase_m = wm * (BM / 2), wbase_n = wn * (BN / 2);
 
-  using LoaderA = TileLoader<BM, AKS>;
-  using LoaderB = TileLoader<BN, BKS>;
+  using LoaderA = StageLoader<BM, TM, AKS>;
+  using LoaderB = StageLoader<BN, TN, BKS>;
   using ReaderA = FragReader<BM, TM, AKS>;
   using ReaderB = FragReader<BN, TN, BKS>;
+  constexpr int NDMA = LoaderA::NCH + LoaderB::NCH;     // transfers per thread per K tile
   LoaderA ldA;
   LoaderB ldB;
-  // Two sets of staging registers: while one set's tile is being written to LDS, the
-  // other set's global loads (two tiles ahead) are still in flight.
-  u32x4 ra[2][LoaderA::NCH], rb[2][LoaderB::NCH];
   ReaderA rdA;
   ReaderB rdB;
   rdA.init(wbase_m, l32, lg);
   rdB.init(wbase_n, l32, lg);
   u32x4 fa[2][TM], fb[2][TN];
   f32x16 acc[TM][TN];
-  const int KT = g.K / BK;      // even: K is a multiple of 128
+  const int KT = g.K / BK;      // a multiple of NSTAGE: K is a multiple of 128
 
-  auto start_tile = [&](const TileCoord& tc) {   // loader state + the first K tile
-    ldA.template init<TM>(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
-    ldB.template init<TN>(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
-    ldA.load(ra[0], 0);
-    ldB.load(rb[0], 0);
+  // Request the first NSTAGE K tiles of an output tile (the whole ring).
+  auto start_tile = [&](const TileCoord& tc) {
+    ldA.init(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
+    ldB.init(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
+#pragma unroll
+    for (int st = 0; st < NSTAGE; ++st) {
+      ldA.issue(st, lds0 + st * STAGE_BYTES);
+      ldB.issue(st, lds0 + st * STAGE_BYTES + A_BYTES);
+    }
   };
 
   auto mfma_slice = [&](int buf) {
@@ -415,56 +414,44 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   constexpr int NDSR = ReaderA::NLOADS + ReaderB::NLOADS;
   constexpr int NPERM = ReaderA::NPERM + ReaderB::NPERM;
 
-  // One 64-deep step on stage kt & 1, software-pipelined over its four 16-deep k slices.
-  // While the MFMAs of slice kk run, the LDS reads of slice kk+1 are in flight; slices 0-2
-  // also move a third of tile kt+1 from its staging set to the other LDS stage, and slices
-  // 1-3 issue the global loads of tile kt+3 into the registers just freed (spread out so
-  // that the 64 B/clk vector-memory path never has to absorb a whole tile at once).  One
-  // barrier per step, after slice 2.
-  // SET: staging set that holds tile kt+1 (= (kt+1) & 1).  STORE: tile kt+1 exists and goes
-  // to the other stage.  LOAD: tile kt+3 exists.
-  auto kstep = [&](int kt, auto set_tag, auto store_tag, auto load_tag) {
-    constexpr int SET = decltype(set_tag)::value;
-    constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
-    const int cur = kt & 1;
-    unsigned char* a_cur = sA(cur); unsigned char* b_cur = sB(cur);
-    unsigned char* a_nxt = sA(cur ^ 1); unsigned char* b_nxt = sB(cur ^ 1);
-    constexpr int P0 = LoaderA::template part_count<0>() + LoaderB::template part_count<0>();
-    constexpr int P1 = LoaderA::template part_count<1>() + LoaderB::template part_count<1>();
-    constexpr int P2 = LoaderA::template part_count<2>() + LoaderB::template part_count<2>();
+  // One 32-deep step on stage ST (K tile j, j % NSTAGE == ST), two 16-deep slices.
+  //   slice 0: MFMAs on fragments 0 | LDS reads of this stage's second slice
+  //            | second half (operand B) of the refill started by the previous step
+  //   wait until K tile j+1 has landed (WAIT transfers may still be in flight), barrier:
+  //            publishes stage ST+1 and retires stage ST
+  //   slice 1: MFMAs on fragments 1 | LDS reads of the next stage's first slice
+  //            | first half (operand A) of the refill of stage ST with K tile j + NSTAGE
+  // REFILL_B / REFILL_A say whether those refills exist; NEXT is false on the last step.
+  auto kstep = [&](int j, auto st_tag, auto refill_b_tag, auto refill_a_tag, auto wait_tag,
+                   auto next_tag) {
+    constexpr int ST = decltype(st_tag)::value;
+    constexpr bool REFILL_B = decltype(refill_b_tag)::value, REFILL_A = decltype(refill_a_tag)::value;
+    constexpr int WAIT = decltype(wait_tag)::value;
+    constexpr bool NEXT = decltype(next_tag)::value;
+    constexpr int PREV = (ST + NSTAGE - 1) % NSTAGE, NXT = (ST + 1) % NSTAGE;
     // slice 0
-    rdA.issue(a_cur, 1); rdB.issue(b_cur, 1);
-    if constexpr (STORE) { ldA.template store_part<0>(ra[SET], a_nxt); ldB.template store_part<0>(rb[SET], b_nxt); }
+    rdA.issue(sA(ST), 1); rdB.issue(sB(ST), 1);
+    if constexpr (REFILL_B) {
+      if (ST != 0 || j > 0) ldB.issue(j - 1 + NSTAGE, lds0 + PREV * STAGE_BYTES + A_BYTES);
+    }
     mfma_slice(0);
     rdA.finish(fa[1]); rdB.finish(fb[1]);
-    interleave_hint<NM, NDSR, STORE ? P0 : 0, 0, NPERM>();
+    interleave_hint<NM, NDSR, NPERM>();
+    if constexpr (NEXT) {
+      // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt<WAIT>();
+      __syncthreads();
+      rdA.issue(sA(NXT), 0); rdB.issue(sB(NXT), 0);
+    }
     // slice 1
-    rdA.issue(a_cur, 2); rdB.issue(b_cur, 2);
-    if constexpr (STORE) { ldA.template store_part<1>(ra[SET], a_nxt); ldB.template store_part<1>(rb[SET], b_nxt); }
-    if constexpr (LOAD) { ldA.template load_part<0>(ra[SET], kt + 3); ldB.template load_part<0>(rb[SET], kt + 3); }
+    if constexpr (REFILL_A) ldA.issue(j + NSTAGE, lds0 + ST * STAGE_BYTES);
     mfma_slice(1);
-    rdA.finish(fa[0]); rdB.finish(fb[0]);
-    interleave_hint<NM, NDSR, STORE ? P1 : 0, LOAD ? P0 : 0, NPERM>();
-    // slice 2
-    rdA.issue(a_cur, 3); rdB.issue(b_cur, 3);
-    if constexpr (STORE) { ldA.template store_part<2>(ra[SET], a_nxt); ldB.template store_part<2>(rb[SET], b_nxt); }
-    if constexpr (LOAD) { ldA.template load_part<1>(ra[SET], kt + 3); ldB.template load_part<1>(rb[SET], kt + 3); }
-    mfma_slice(0);
-    rdA.finish(fa[1]); rdB.finish(fb[1]);
-    interleave_hint<NM, NDSR, STORE ? P2 : 0, LOAD ? P1 : 0, NPERM>();
-    if constexpr (STORE) __syncthreads();
-    // slice 3
-    if constexpr (STORE) { rdA.issue(a_nxt, 0); rdB.issue(b_nxt, 0); }
-    if constexpr (LOAD) { ldA.template load_part<2>(ra[SET], kt + 3); ldB.template load_part<2>(rb[SET], kt + 3); }
-    mfma_slice(1);
-    if constexpr (STORE) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
-    interleave_hint<NM, STORE ? NDSR : 0, 0, LOAD ? P2 : 0, STORE ? NPERM : 0>();
+    if constexpr (NEXT) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
+    interleave_hint<NM, NEXT ? NDSR : 0, NEXT ? NPERM : 0>();
   };
   using T = std::true_type;
   using F = std::false_type;
-  using S0 = std::integral_constant<int, 0>;
-  using S1 = std::integral_constant<int, 1>;
-
   TileCoord tc = decode(logical);
   start_tile(tc);
   while (true) {
@@ -475,38 +462,43 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // K tile 1 -> set 1; K tile 0 -> LDS stage 0 (every wave has left the previous tile's
-    // step KT-2, the last one that read stage 0, through that step's barrier); K tile 2 ->
-    // set 0.
-    ldA.load(ra[1], 1);
-    ldB.load(rb[1], 1);
-    ldA.store(ra[0], sA(0));
-    ldB.store(rb[0], sB(0));
-    if (KT > 2) {
-      ldA.load(ra[0], 2);
-      ldB.load(rb[0], 2);
-    }
+    // K tile 0 must have landed.  The previous tile's stores are in flight as well, and
+    // stores and loads complete out of order with each other, so wait for everything.
+    // The wait is issued through the builtin so that the compiler's own bookkeeping also
+    // sees every earlier vector-memory operation (spill reloads included) as complete and
+    // inserts no waits of its own inside the K loop.
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0), other counters unconstrained
     __syncthreads();
     rdA.issue(sA(0), 0);
     rdB.issue(sB(0), 0);
     rdA.finish(fa[0]);
     rdB.finish(fb[0]);
 
-    int kt = 0;
-    for (; kt + 4 < KT; kt += 2) {
-      kstep(kt, S1{}, T{}, T{});
-      kstep(kt + 1, S0{}, T{}, T{});
+    // Steady state: at the barrier of step j the transfers issued after K tile j+1 are the
+    // two younger K tiles = 2 * NDMA per thread.
+    int j = 0;
+    for (; j + 2 * NSTAGE <= KT; j += NSTAGE) {
+      kstep(j + 0, I<0>{}, T{}, T{}, I<2 * NDMA>{}, T{});
+      kstep(j + 1, I<1>{}, T{}, T{}, I<2 * NDMA>{}, T{});
+      kstep(j + 2, I<2>{}, T{}, T{}, I<2 * NDMA>{}, T{});
+      kstep(j + 3, I<3>{}, T{}, T{}, I<2 * NDMA>{}, T{});
     }
-    if (kt + 4 == KT) {            // four steps left: only the first still has a tile to fetch
-      kstep(kt, S1{}, T{}, T{});
-      kstep(kt + 1, S0{}, T{}, F{});
-      kt += 2;
-    }
-    kstep(kt, S1{}, T{}, F{});     // two steps left
-    kstep(kt + 1, S0{}, F{}, F{});
+    // Last ring: nothing left to request except the second half of the refill begun by the
+    // step before; fewer and fewer transfers remain in flight.
+    kstep(j + 0, I<0>{}, T{}, F{}, I<2 * NDMA>{}, T{});
+    kstep(j + 1, I<1>{}, F{}, F{}, I<NDMA>{}, T{});
+    kstep(j + 2, I<2>{}, F{}, F{}, I<0>{}, T{});
+    kstep(j + 3, I<3>{}, F{}, F{}, I<0>{}, F{});
 
     const int next = logical + g.wg_per_xcd;
     const bool more = next < range_end;
+    TileCoord tn = tc;
+    if (more) {
+      // every wavefront must be done reading the ring before it is refilled
+      __syncthreads();
+      tn = decode(next);
+      start_tile(tn);
+    }
     float alpha = g.alpha;
     if (g.bscale) {
       const float sc = g.bscale[tc.b];
@@ -514,17 +506,11 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
     }
     // the diagonal crosses this tile only if its row and column ranges overlap
     const bool on_diag = g.gamma != 0.f && tc.m0 < tc.n0 + BN && tc.n0 < tc.m0 + BM;
-#ifdef MLC_PROBE_SKIP_EPILOGUE
-    if (alpha == 12345.f)
-#endif
-    {
-      if (g.C) store_tile<TM, TN, true>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
-      else store_tile<TM, TN, false>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
-    }
+    if (g.C) store_tile<TM, TN, true>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
+    else store_tile<TM, TN, false>(g, acc, tc, alpha, on_diag, wbase_m, wbase_n, l32, lg);
     if (!more) break;
     logical = next;
-    tc = decode(logical);
-    start_tile(tc);
+    tc = tn;
   }
 }
 
@@ -565,7 +551,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
   g.alpha = d.alpha; g.beta = d.beta; g.gamma = d.gamma;
   g.bscale = d.bscale; g.bscale_pow = d.bscale_pow;
-  const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
+  const size_t lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
   auto kern = ns_gemm_bf16_kernel<BM, BN, AKS, BKS>;
   static bool attr_set = false;   // per instantiation; raising the LDS limit is idempotent
   if (!attr_set) {
@@ -592,7 +578,7 @@ int launch_layout(const GemmDesc& d, hipStream_t stream) {
 }  // namespace
 
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream) {
-  if (d.M % 128 || d.N % 128 || d.K % (2 * BK) || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0)
+  if (d.M % 128 || d.N % 128 || d.K % (NSTAGE * BK) || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0)
     return MLC_ERR_SHAPE;
   if ((d.lda | d.ldb | d.ldd | d.strideA | d.strideB | d.strideD) % 8) return MLC_ERR_SHAPE;
   if (d.C && ((d.ldc | d.strideC) % 8)) return MLC_ERR_SHAPE;
