@@ -58,3 +58,15 @@ def assert_stored_close(got_t: torch.Tensor, ref: np.ndarray, what: str):
         assert_bf16_rounding_of(got_t, ref, what)
     else:
         assert_fp32_close(got_t, ref, what)
+
+
+def update_error_bf16(W_gpu_t: torch.Tensor, W0: np.ndarray, W_ref: np.ndarray) -> float:
+    """Relative Frobenius error of the update when the result was stored in bf16.
+
+    W_gpu - W_ref = (storage rounding, |.| <= ulp/2, mean square ulp^2/12, independent of the
+    update) + (error of the update).  The rounding part is removed in quadrature with its
+    expectation, which is far tighter than allowing half an ulp per element."""
+    d = to_f64(W_gpu_t) - W_ref
+    ulp = storage.bf16_ulp(W_ref)
+    excess = float(np.sum(d * d) - np.sum(ulp * ulp) / 12.0)
+    return float(np.sqrt(max(excess, 0.0)) / np.linalg.norm(W_ref - W0))
