@@ -391,6 +391,14 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
     WorkerPtrs w; CodePtrs c; ScalePtrs s;
     gather_ptrs(g, hp->K, hp->quant_bits != 0, w, c, s);
     if (hp->quant_bits) {
+      // one pass when the row fits in registers, else quantise and then consume the codes
+      rc = launch_quantize_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype,
+                                       g.outer_momentum, c, s, g.count * g.m, g.n, hp->K, hp->eta_out,
+                                       hp->mu, hp->nesterov, hp->write_back, stream);
+      if (rc != MLC_ERR_UNSUPPORTED) {
+        if (rc != MLC_OK) return rc;
+        continue;
+      }
       rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, g.count * g.m,
                            g.n, hp->K, stream);
       if (rc != MLC_OK) return rc;

@@ -97,6 +97,10 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
 int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
                     const CodePtrs& codes, const ScalePtrs& scales, int64_t rows, int64_t n,
                     int K, hipStream_t stream);
+int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
+                                float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
+                                int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
+                                hipStream_t stream);
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                          float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
                          int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,

@@ -146,6 +146,157 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
   }
 }
 
+// Single-pass variant: a group of G threads (a wavefront or the whole workgroup) owns a row
+// and keeps it in registers (NV vectors of 8 elements per thread), so theta_g is read once
+// for all K workers and every theta_k exactly once.  Same arithmetic as above.
+template <typename WT, typename GT, int NV, int G>
+__global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
+    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, long rows, int n,
+    int K) {
+  constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
+  __shared__ float red[2][OT_THREADS / 64];
+  const int t = threadIdx.x % G;
+  const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
+  const bool live = row < rows;            // whole groups are live or not; no early return
+  const long rbase = live ? row * n : 0;   // (the workgroup-wide barrier below needs everyone)
+  float tg[NV][8];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (t + i * G) * 8;
+    if (live && c < n) Ld<GT>::load8(theta_g + rbase + c, tg[i]);
+    else
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tg[i][j] = 0.f;
+  }
+  for (int k = 0; k < K; ++k) {
+    const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
+    float d[NV][8];
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (t + i * G) * 8;
+      if (live && c < n) {
+        float b[8];
+        Ld<WT>::load8(tk + c, b);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          d[i][j] = tg[i][j] - b[j];
+          amax = fmaxf(amax, fabsf(d[i][j]));
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) d[i][j] = 0.f;
+      }
+    }
+    amax = wave_max(amax);
+    if constexpr (G > 64) {
+      if ((threadIdx.x & 63) == 0) red[k & 1][threadIdx.x >> 6] = amax;
+      __syncthreads();
+      amax = fmaxf(fmaxf(red[k & 1][0], red[k & 1][1]), fmaxf(red[k & 1][2], red[k & 1][3]));
+    }
+    const float scale = amax / 7.0f;
+    if (live && t == 0) scales.p[k][row] = scale;
+    uint8_t* crow = codes.p[k] + row * (long)(n / 2);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (t + i * G) * 8;
+      if (live && c < n) {
+        unsigned int packed = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int q = (amax > 0.f) ? quant_level(d[i][j], scale) : 0;
+          packed |= (unsigned int)(q + 8) << (4 * j);
+        }
+        *reinterpret_cast<unsigned int*>(crow + c / 2) = packed;
+      }
+    }
+  }
+}
+
+// Quantiser and outer update in one pass over a row held in registers: codes and scales are
+// written as the stand-alone quantiser writes them, and the dequantised deltas go straight
+// into the mean and eq. 3 without re-reading theta_g or the codes.
+template <typename WT, typename GT, int NV, int G>
+__global__ __launch_bounds__(OT_THREADS) void quantize_outer_rows_kernel(
+    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
+    long rows, int n, int K, float eta, float mu, float inv_k, int nesterov, int write_back) {
+  constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
+  __shared__ float red[2][OT_THREADS / 64];
+  const int t = threadIdx.x % G;
+  const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
+  const bool live = row < rows;
+  const long rbase = live ? row * n : 0;
+  float tg[NV][8], acc[NV][8];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (t + i * G) * 8;
+    if (live && c < n) Ld<GT>::load8(theta_g + rbase + c, tg[i]);
+    else
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tg[i][j] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+  }
+  for (int k = 0; k < K; ++k) {
+    const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
+    float d[NV][8];
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (t + i * G) * 8;
+      if (live && c < n) {
+        float b[8];
+        Ld<WT>::load8(tk + c, b);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          d[i][j] = tg[i][j] - b[j];
+          amax = fmaxf(amax, fabsf(d[i][j]));
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) d[i][j] = 0.f;
+      }
+    }
+    amax = wave_max(amax);
+    if constexpr (G > 64) {
+      if ((threadIdx.x & 63) == 0) red[k & 1][threadIdx.x >> 6] = amax;
+      __syncthreads();
+      amax = fmaxf(fmaxf(red[k & 1][0], red[k & 1][1]), fmaxf(red[k & 1][2], red[k & 1][3]));
+    }
+    const float scale = amax / 7.0f;
+    if (live && t == 0) scales.p[k][row] = scale;
+    uint8_t* crow = codes.p[k] + row * (long)(n / 2);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (t + i * G) * 8;
+      if (live && c < n) {
+        unsigned int packed = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int q = (amax > 0.f) ? quant_level(d[i][j], scale) : 0;
+          packed |= (unsigned int)(q + 8) << (4 * j);
+          acc[i][j] += __fmul_rn((float)q, scale);
+        }
+        *reinterpret_cast<unsigned int*>(crow + c / 2) = packed;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (t + i * G) * 8;
+    if (live && c < n) {
+      float uv[8];
+      Ld<float>::load8(u + rbase + c, uv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j] * inv_k, eta, mu, nesterov);
+      Ld<GT>::store8(theta_g + rbase + c, tg[i]);
+      Ld<float>::store8(u + rbase + c, uv);
+      if (write_back)
+        for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + rbase + c, tg[i]);
+    }
+  }
+}
+
 // ---- dequantise + average + outer update --------------------------------------------
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
@@ -240,6 +391,32 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
                        (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_QUANTIZE, stream, 0.0, bytes);
   const bool vec = n % 8 == 0;
+  // single-pass register kernel: a wavefront per row up to 2048 columns, a workgroup per row
+  // up to 24576; otherwise (or for odd row lengths) the two-pass kernel
+  if (vec && n <= 24576 && !(worker_dtype == MLC_F32 && global_dtype == MLC_BF16)) {
+    const int g = n <= 2048 ? 64 : OT_THREADS;
+    const int need = (int)((n + g * 8 - 1) / (g * 8));
+    const int nv = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : need <= 8 ? 8 : 12;
+    const long rpb = OT_THREADS / g;
+    const long nblk = (rows + rpb - 1) / rpb;
+#define MLC_QR(WT, GT, NV, G)                                                                     \
+  hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G>), dim3((unsigned)nblk),              \
+                     dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, (long)rows, \
+                     (int)n, K)
+#define MLC_QR_NV(WT, GT)                                                                         \
+  do {                                                                                            \
+    if (g == 64) { if (nv == 1) MLC_QR(WT, GT, 1, 64); else if (nv == 2) MLC_QR(WT, GT, 2, 64);   \
+                   else MLC_QR(WT, GT, 4, 64); }                                                  \
+    else { if (nv <= 2) MLC_QR(WT, GT, 2, 256); else if (nv == 4) MLC_QR(WT, GT, 4, 256);         \
+           else if (nv == 8) MLC_QR(WT, GT, 8, 256); else MLC_QR(WT, GT, 12, 256); }              \
+  } while (0)
+    if (worker_dtype == MLC_BF16 && global_dtype == MLC_F32) MLC_QR_NV(bf16_t, float);
+    else if (worker_dtype == MLC_BF16) MLC_QR_NV(bf16_t, bf16_t);
+    else MLC_QR_NV(float, float);
+#undef MLC_QR_NV
+#undef MLC_QR
+    return check_launch();
+  }
 #define MLC_CALL(WT, GT)                                                                          \
   do {                                                                                            \
     if (vec)                                                                                      \
@@ -281,6 +458,43 @@ int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, i
   } while (0)
   MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
 #undef MLC_CALL
+  return check_launch();
+}
+
+// Returns MLC_ERR_UNSUPPORTED when the one-pass kernel does not cover the request (the
+// caller then runs the quantiser and the dequantising update as two launches).
+int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
+                                float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
+                                int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
+                                hipStream_t stream) {
+  if (n % 8 || n > 16384 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
+    return MLC_ERR_UNSUPPORTED;
+  const int g = n <= 2048 ? 64 : OT_THREADS;
+  const int need = (int)((n + g * 8 - 1) / (g * 8));
+  const int nv = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
+  const long rpb = OT_THREADS / g;
+  const long nblk = (rows + rpb - 1) / rpb;
+  if (nblk > 0x7fffffffL) return MLC_ERR_SHAPE;
+  const double bytes = (double)rows * n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + 0.5 * K +
+                                           2 * esize(global_dtype) + 8) + (double)rows * 4 * K;
+  LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
+  const float inv_k = 1.0f / (float)K;
+#define MLC_QO(WT, GT, NV, G)                                                                     \
+  hipLaunchKernelGGL((quantize_outer_rows_kernel<WT, GT, NV, G>), dim3((unsigned)nblk),            \
+                     dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, (long)rows,   \
+                     (int)n, K, eta_out, mu, inv_k, nesterov, write_back)
+#define MLC_QO_NV(WT, GT)                                                                         \
+  do {                                                                                            \
+    if (g == 64) { if (nv == 1) MLC_QO(WT, GT, 1, 64); else if (nv == 2) MLC_QO(WT, GT, 2, 64);   \
+                   else MLC_QO(WT, GT, 4, 64); }                                                  \
+    else { if (nv <= 2) MLC_QO(WT, GT, 2, 256); else if (nv == 4) MLC_QO(WT, GT, 4, 256);         \
+           else MLC_QO(WT, GT, 8, 256); }                                                         \
+  } while (0)
+  if (worker_dtype == MLC_BF16 && global_dtype == MLC_F32) MLC_QO_NV(bf16_t, float);
+  else if (worker_dtype == MLC_BF16) MLC_QO_NV(bf16_t, bf16_t);
+  else MLC_QO_NV(float, float);
+#undef MLC_QO_NV
+#undef MLC_QO
   return check_launch();
 }
 

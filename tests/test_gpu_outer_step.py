@@ -64,6 +64,11 @@ QCASES = [
     (1, 9, 6, 3, torch.float32, torch.float32),           # short rows: scalar path
     (1, 40, 2560, 4, torch.bfloat16, torch.bfloat16),     # a 3.1B-scale row length
     (1, 16, 10240, 1, torch.bfloat16, torch.float32),
+    (1, 6, 20480, 2, torch.bfloat16, torch.float32),      # 15B-scale row length
+    (1, 10, 5120, 3, torch.bfloat16, torch.float32),
+    (2, 9, 2048, 2, torch.float32, torch.float32),        # widest wavefront-per-row case
+    (1, 5, 24584, 1, torch.bfloat16, torch.float32),      # beyond the register kernel: two-pass path
+    (1, 7, 520, 2, torch.float32, torch.bfloat16),        # dtype pair served by the two-pass path
 ]
 
 
@@ -97,8 +102,10 @@ def test_quantised_outer_step_codes_bit_exact(cnt, m, n, K, wd, gd):
     torch.cuda.synchronize()
     assert_fp32_close(u.cpu().reshape(-1, n), ref["u"], "outer momentum (quantised)")
     assert_stored_close(tg.cpu().reshape(-1, n), ref["theta"], "global parameters (quantised)")
-    for k in range(K):
-        assert_stored_close(ws[k].cpu().reshape(-1, n), ref["theta"], f"worker {k} write-back")
+    for k in range(K):   # theta_k <- theta_g: exactly what the global buffer now holds
+        assert torch.equal(ws[k].cpu(), tg.cpu().to(wd)), f"worker {k} write-back differs from theta_g"
+        if not (wd == torch.float32 and gd == torch.bfloat16):
+            assert_stored_close(ws[k].cpu().reshape(-1, n), ref["theta"], f"worker {k} write-back")
 
 
 def test_streaming_fragments_equal_one_call():
