@@ -72,6 +72,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--workspace-gb", type=float, default=None)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives); "
@@ -104,6 +107,14 @@ def main() -> int:
         for layer in range(n_layers):          # a8 + a9 as a10: one layer fragment per call
             mlc.muloco_outer_step(job.layer_fragment(layer, quant=True), hp)
 
+    if args.calibration_copy:
+        src = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -116,6 +127,20 @@ def main() -> int:
     wall = time.perf_counter() - t0
     timing = mlc.muloco_timing_read()
     mlc.muloco_timing_enable(False)
+
+    # Outside the timed region: the stand-alone compressor (codes only), so that it has a
+    # figure of its own (inside a step it runs fused with the outer update when rows fit in
+    # registers).
+    mlc.muloco_timing_enable(True)
+    mlc.muloco_timing_read()
+    for _ in range(3):
+        mlc.muloco_quantize_delta(job.outer_groups(quant=True), job.outer_hparams(quant_bits=4))
+    torch.cuda.synchronize()
+    extra = mlc.muloco_timing_read()
+    mlc.muloco_timing_enable(False)
+    q = extra["quantize"]
+    quant_alone = {"ms": q["total_ms"] / 3, "GBps": q["bytes"] / (q["total_ms"] * 1e-3) * 1e-9 if q["total_ms"] > 0 else 0.0}
+    quant_alone["frac_hbm"] = quant_alone["GBps"] / PEAK_HBM_GBS
 
     ms_per_step = wall * 1e3 / args.steps
     gemm = timing["ns_gemm"]
@@ -134,8 +159,18 @@ def main() -> int:
         "ns_gemm_launches_per_step": gemm["launches"] / args.steps,
         "ns_flop_per_step": gemm["flops"] / args.steps,
         "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
-        "quantize": fam("quantize"), "dequant_outer": fam("dequant_outer"),
+        "quantize_outer_fused": fam("dequant_outer"),
+        "quantize_standalone_whole_model": quant_alone,
+        "nominal_ns_tflops_equivalent": None,
     }
+    nominal = job.ns_flops() * job.K
+    breakdown["nominal_ns_tflops_equivalent"] = nominal / (gemm["total_ms"] / args.steps * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"ns_gemm_bf16_kernel_{wl.name}_traffic.txt")
+    if os.path.exists(tpath):       # HBM bytes per launch from the rocprofv3 --pmc runs
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
     out = {
         "metric": METRIC,
         "value": ns_tflops,
@@ -154,11 +189,21 @@ def main() -> int:
                    "params_2d": wl.n_params(), "ns_iters": 5,
                    "step": "muon inner step + fused outer step + 4-bit quantised outer step per layer fragment"},
         "roofline": {"bound": "mfma", "achieved": ns_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ns_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": ns_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "kernel": "ns_gemm_bf16_kernel",
                      "avg_launch_ms": gemm["total_ms"] / max(1, gemm["launches"])},
         "breakdown": breakdown,
     }
+    # Achievable peaks of this chip from the microbenchmark executable (a child process).
+    try:
+        import subprocess
+        from paper_2505_23725_amd.build import MICROBENCH_PATH
+        res = subprocess.run([MICROBENCH_PATH], capture_output=True, text=True, timeout=120)
+        out["achievable"] = json.loads(res.stdout.strip().splitlines()[-1])
+        ach = out["achievable"]["mfma_bf16_tflops_random_operands"]
+        out["roofline"]["frac_of_achievable"] = ns_tflops / ach if ach > 0 else None
+    except Exception as e:      # the benchmark stands without it
+        out["achievable"] = {"error": str(e)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_budget)
     print(json.dumps(out))

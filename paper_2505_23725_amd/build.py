@@ -9,6 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmuloco.so")
+MICROBENCH_PATH = os.path.join(HERE, "mlc_microbench")
 SOURCES = ["api.hip", "ns_gemm.hip", "inner_elementwise.hip", "outer.hip"]
 
 HIPCC_FLAGS = [
@@ -40,7 +41,21 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    build_microbench(verbose)
     return LIB_PATH
+
+
+def build_microbench(verbose: bool = True) -> str:
+    """Achievable-peak microbenchmark (stand-alone executable used by bench.py)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-value",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "microbench.hip"), "-o", MICROBENCH_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on microbench.hip:\n" + res.stderr)
+    return MICROBENCH_PATH
 
 
 if __name__ == "__main__":

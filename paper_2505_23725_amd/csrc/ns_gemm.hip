@@ -440,7 +440,11 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
     if constexpr (NEXT) {
       // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
       __builtin_amdgcn_sched_barrier(0);
+#ifdef MLC_PROBE_WAIT0
+      wait_vmcnt<0>();
+#else
       wait_vmcnt<WAIT>();
+#endif
       __syncthreads();
       rdA.issue(sA(NXT), 0); rdB.issue(sB(NXT), 0);
     }
