@@ -440,11 +440,7 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
     if constexpr (NEXT) {
       // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
       __builtin_amdgcn_sched_barrier(0);
-#ifdef MLC_PROBE_WAIT0
-      wait_vmcnt<0>();
-#else
       wait_vmcnt<WAIT>();
-#endif
       __syncthreads();
       rdA.issue(sA(NXT), 0); rdB.issue(sB(NXT), 0);
     }
@@ -547,11 +543,7 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   g.tiles_per_xcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
   // one workgroup per CU for the 256 x 256 tile (128 KiB of LDS each), two for 128 x 128
   const int per_cu = (BM == 256) ? 1 : 2;
-#ifdef MLC_PROBE_NONPERSISTENT
-  g.wg_per_xcd = g.tiles_per_xcd; (void)per_cu;
-#else
   g.wg_per_xcd = cus_per_xcd() * per_cu;
-#endif
   if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
   g.alpha = d.alpha; g.beta = d.beta; g.gamma = d.gamma;
   g.bscale = d.bscale; g.bscale_pow = d.bscale_pow;
