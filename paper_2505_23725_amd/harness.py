@@ -36,6 +36,12 @@ class MulocoJob:
         self.gen_dev = "cpu" if generate_on == "cpu" else self.device
         self.theta_g: List[torch.Tensor] = []
         self.u: List[torch.Tensor] = []
+        # The K replicas of a shape group are stacked in one [K, count, m, n] tensor, so the
+        # inner step can hand all K * count matrices of a shape to the library as one group
+        # (one launch per kernel kind); workers[k][gi] etc. are views of replica k.
+        self.W: List[torch.Tensor] = []
+        self.M: List[torch.Tensor] = []
+        self.G: List[torch.Tensor] = []
         self.workers: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
         self.mom: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
         self.grad: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
@@ -43,17 +49,22 @@ class MulocoJob:
             init = self._draw(shp, S.PARAM_STD, 100 + gi, self.pdtype)   # theta^(0), worker dtype
             self.theta_g.append(init.to(torch.float32))
             self.u.append(torch.zeros(shp, dtype=torch.float32, device=self.device))
+            self.W.append(torch.empty((self.K,) + tuple(shp), dtype=self.pdtype, device=self.device))
+            self.M.append(torch.zeros((self.K,) + tuple(shp), dtype=torch.float32, device=self.device))
+            self.G.append(torch.zeros((self.K,) + tuple(shp), dtype=self.gdtype, device=self.device))
             for k in range(self.K):
-                self.workers[k].append(init.clone())
-                self.mom[k].append(torch.zeros(shp, dtype=torch.float32, device=self.device))
-                self.grad[k].append(torch.zeros(shp, dtype=self.gdtype, device=self.device))
+                self.W[gi][k].copy_(init)
+                self.workers[k].append(self.W[gi][k])
+                self.mom[k].append(self.M[gi][k])
+                self.grad[k].append(self.G[gi][k])
+            del init
         self.codes = self.scales = None
         if with_quant:
             self.codes = [[torch.empty((c * m, n // 2), dtype=torch.uint8, device=self.device)
                            for (c, m, n) in self.shapes] for _ in range(self.K)]
             self.scales = [[torch.empty((c * m,), dtype=torch.float32, device=self.device)
                             for (c, m, n) in self.shapes] for _ in range(self.K)]
-        need = max(B.newton_schulz_workspace_bytes(*s) for s in self.shapes)
+        need = max(B.newton_schulz_workspace_bytes(self.K * s[0], s[1], s[2]) for s in self.shapes)
         floor = max(B.newton_schulz_workspace_min_bytes(s[1], s[2]) for s in self.shapes)
         if workspace_cap_bytes is not None:
             need = max(floor, min(need, workspace_cap_bytes))
@@ -87,9 +98,18 @@ class MulocoJob:
         return math.sqrt(n / m)
 
     def inner_groups(self, k: int) -> List[B.InnerGroup]:
+        """Groups of replica k only."""
         return [B.InnerGroup(self.workers[k][gi], self.grad[k][gi], self.mom[k][gi],
                              self.lr_scale(m, n))
                 for gi, (c, m, n) in enumerate(self.shapes)]
+
+    def inner_groups_all(self) -> List[B.InnerGroup]:
+        """One group per shape holding the matrices of all K replicas: K * count matrices."""
+        out = []
+        for gi, (c, m, n) in enumerate(self.shapes):
+            out.append(B.InnerGroup(self.W[gi].view(self.K * c, m, n), self.G[gi].view(self.K * c, m, n),
+                                    self.M[gi].view(self.K * c, m, n), self.lr_scale(m, n)))
+        return out
 
     def outer_groups(self, quant: bool = False, group_ids=None) -> List[B.OuterGroup]:
         ids = range(len(self.shapes)) if group_ids is None else group_ids
@@ -131,15 +151,14 @@ class MulocoJob:
 
     # -- the hot path -----------------------------------------------------------------------
     def inner_step(self) -> None:
-        hp = self.muon_hparams()
-        for k in range(self.K):
-            B.muloco_inner_step(self.inner_groups(k), hp, self.workspace)
+        """One Muon step of every replica: same-shape matrices of all replicas share launches."""
+        B.muloco_inner_step(self.inner_groups_all(), self.muon_hparams(), self.workspace)
 
     def outer_step(self, quant_bits: int = 0) -> None:
         B.muloco_outer_step(self.outer_groups(quant=quant_bits != 0), self.outer_hparams(quant_bits))
 
     def ns_flops(self, iters: int = 5) -> float:
-        """Matrix-core FLOP the library executes for one inner step of one replica."""
+        """Nominal Newton-Schulz FLOP (4 s^2 l + 2 s^3 per iteration) of one replica's inner step."""
         tot = 0.0
         for (c, m, n) in self.shapes:
             mp, np_ = -(-m // 128) * 128, -(-n // 128) * 128
