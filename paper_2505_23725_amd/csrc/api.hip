@@ -140,10 +140,10 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
     int rc = launch_ns_gemm(g, stream);
     if (rc != MLC_OK) return rc;
     // Polynomial: B' = c A A + b A + a I.  A is symmetric, so either operand may be read
-    // along rows or along columns; the K-strided LDS path is the faster one.
+    // along rows or along columns; the K-contiguous LDS path is the faster one.
     g = GemmDesc{};
-    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 1;
-    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 1;
+    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
+    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
     g.D = w.B; g.ldd = p.sp; g.strideD = ss;
     g.C = w.A; g.ldc = p.sp; g.strideC = ss;
     g.M = g.N = g.K = (int)p.sp; g.batch = (int)chunk;

@@ -5,12 +5,17 @@
 // (BM/2) x (BN/2) block of the output tile as TM x TN accumulators of v_mfma_f32_32x32x16_bf16.
 //
 // Operand tiles travel HBM -> LDS directly (buffer_load ... lds): no staging registers, no
-// LDS store instructions.  The LDS holds a ring of four 32-deep stages; a stage is refilled
-// as soon as every wavefront has read it, three stages (96 k) ahead of its use, and all four
-// stages of the next output tile are requested before the current tile's epilogue.  The
-// compiler does not model these transfers, so their completion is awaited explicitly
-// (s_waitcnt vmcnt(n): a wavefront's vector-memory loads complete in issue order) before the
-// barrier that publishes a stage.
+// LDS store instructions.  The LDS holds a ring of five 32-deep stages (all 160 KiB of a CU
+// for the 256 x 256 tile).  K tiles are requested in pairs (2i, 2i+1), row by row with the
+// two requests of a row back to back: a K-contiguous operand row contributes 64 bytes per
+// K tile, half a 128-byte cache line, and the vector L1 merges the second half into the
+// line fill the first one started, which halves the requests the L2 has to serve.  A pair
+// is requested as soon as both of its stages are free, two to three K tiles ahead of its
+// use; with five stages that is as far ahead as a four-stage ring of single tiles.  The
+// first four K tiles of the next output tile are requested before the current tile's
+// epilogue.  The compiler does not model these transfers, so their completion is awaited
+// explicitly (s_waitcnt vmcnt(n): a wavefront's vector-memory loads complete in issue
+// order) before the barrier that publishes a stage.
 //
 // An operand whose K index is the slow one in memory ("K-strided": X in B'X for wide
 // matrices, both operands of X^T X for tall ones) is never transposed in HBM.  Its tile is
@@ -36,7 +41,8 @@ template <int V> using I = std::integral_constant<int, V>;
 namespace {
 
 constexpr int BK = 32;           // K depth of one LDS stage
-constexpr int NSTAGE = 4;        // stages in the LDS ring
+constexpr int NSTAGE = 5;        // stages in the LDS ring
+constexpr int NPRE = 4;          // K tiles requested when an output tile starts
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 
@@ -120,19 +126,17 @@ struct StageLoader {
       k_stride = (unsigned int)(BK * ld * 2);
     }
   }
-  // all NCH transfers of K tile kt into the stage at LDS byte offset `stage`
-  __device__ __forceinline__ void issue(int kt, unsigned int stage) const {
-#pragma unroll
-    for (int it = 0; it < NCH; ++it)
-      dma16(rsrc, voff, kt * k_stride + it * it_stride, stage + it * 4096 + wave_lds);
+  // transfer `it` (of NCH) of K tile kt into the stage at LDS byte offset `stage`
+  __device__ __forceinline__ void issue_one(int kt, unsigned int stage, int it) const {
+    dma16(rsrc, voff, kt * k_stride + it * it_stride, stage + it * 4096 + wave_lds);
   }
 };
 
 // ---- LDS -> MFMA fragments ------------------------------------------------------------
 // Reading one operand's fragments for one 16-deep k slice is split in two so that the LDS
 // reads can be issued one slice ahead of the MFMAs that consume them:
-//   issue()  : LDS loads into raw registers
-//   finish() : raw registers -> TT fragments of 8 bf16 (a no-op for K-contiguous tiles,
+//   issue_part() : LDS loads into raw registers
+//   finish()     : raw registers -> TT fragments of 8 bf16 (a no-op for K-contiguous tiles,
 //              sixteen-bit regrouping for K-strided ones)
 // K-strided stage: [32][R] bf16; a lane reads its TT adjacent rows for each of its 8 k.
 // One v_perm_b32 each: the low (high) 16-bit halves of x and y, x in the low half.
@@ -158,11 +162,14 @@ struct FragReader {
     lane_swz = (l32 >> 2) & 3;
     lane_lg = lg;
   }
-  __device__ __forceinline__ void issue(const unsigned char* stage, int kk) {
+  // Part PART of NPARTS of the LDS reads of k slice kk (the parts are issued between the
+  // transfers of a refill so that neither kind of request arrives in a burst).
+  template <int PART, int NPARTS>
+  __device__ __forceinline__ void issue_part(const unsigned char* stage, int kk) {
     if constexpr (KS) {
       const unsigned char* p = stage + off + kk * 16 * (R * 2);
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
+      for (int t = PART * 8 / NPARTS; t < (PART + 1) * 8 / NPARTS; ++t) {
         if constexpr (TT == 2) {
           raw[t] = *reinterpret_cast<const unsigned int*>(p + t * (R * 2));
         } else {
@@ -174,7 +181,7 @@ struct FragReader {
     } else {
       const int chunk = ((kk * 2 + lane_lg) ^ lane_swz) << 4;
 #pragma unroll
-      for (int t = 0; t < TT; ++t) {               // row TT * l32 + t is 4 slots (256 B) per t
+      for (int t = PART * TT / NPARTS; t < (PART + 1) * TT / NPARTS; ++t) {   // row TT * l32 + t: 256 B per t
         const u32x4 v = *reinterpret_cast<const u32x4*>(stage + off + t * 256 + chunk);
         raw[4 * t] = v.x; raw[4 * t + 1] = v.y; raw[4 * t + 2] = v.z; raw[4 * t + 3] = v.w;
       }
@@ -341,8 +348,6 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const unsigned int lds0 =
       (unsigned int)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem;
-  auto sA = [&](int st) { return smem + st * STAGE_BYTES; };
-  auto sB = [&](int st) { return smem + st * STAGE_BYTES + A_BYTES; };
 
   const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
   const int range_end = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
@@ -388,16 +393,24 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   rdB.init(wbase_n, l32, lg);
   u32x4 fa[2][TM], fb[2][TN];
   f32x16 acc[TM][TN];
-  const int KT = g.K / BK;      // a multiple of NSTAGE: K is a multiple of 128
+  const int KT = g.K / BK;      // a multiple of 4: K is a multiple of 128
 
-  // Request the first NSTAGE K tiles of an output tile (the whole ring).
+  // Request the first NPRE K tiles of an output tile into stages 0 .. NPRE-1, as pairs.
   auto start_tile = [&](const TileCoord& tc) {
     ldA.init(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
     ldB.init(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
 #pragma unroll
-    for (int st = 0; st < NSTAGE; ++st) {
-      ldA.issue(st, lds0 + st * STAGE_BYTES);
-      ldB.issue(st, lds0 + st * STAGE_BYTES + A_BYTES);
+    for (int st = 0; st < NPRE; st += 2) {
+#pragma unroll
+      for (int it = 0; it < LoaderA::NCH; ++it) {
+        ldA.issue_one(st, lds0 + st * STAGE_BYTES, it);
+        ldA.issue_one(st + 1, lds0 + (st + 1) * STAGE_BYTES, it);
+      }
+#pragma unroll
+      for (int it = 0; it < LoaderB::NCH; ++it) {
+        ldB.issue_one(st, lds0 + st * STAGE_BYTES + A_BYTES, it);
+        ldB.issue_one(st + 1, lds0 + (st + 1) * STAGE_BYTES + A_BYTES, it);
+      }
     }
   };
 
@@ -413,42 +426,85 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   constexpr int NM = TM * TN;
   constexpr int NDSR = ReaderA::NLOADS + ReaderB::NLOADS;
   constexpr int NPERM = ReaderA::NPERM + ReaderB::NPERM;
+  static_assert(TM == TN && LoaderA::NCH == TM && LoaderB::NCH == TN, "square tiles: one transfer per part");
 
-  // One 32-deep step on stage ST (K tile j, j % NSTAGE == ST), two 16-deep slices.
-  //   slice 0: MFMAs on fragments 0 | LDS reads of this stage's second slice
-  //            | second half (operand B) of the refill started by the previous step
-  //   wait until K tile j+1 has landed (WAIT transfers may still be in flight), barrier:
-  //            publishes stage ST+1 and retires stage ST
+  // LDS reads of k slice kk of the stage at byte offset `st`, in TM parts; part P is
+  // followed by the two transfers extra(P) issues (or none).
+  auto reads = [&](unsigned int st, int kk, auto&& extra) {
+    auto part = [&](auto p_tag) {
+      constexpr int P = decltype(p_tag)::value;
+      rdA.template issue_part<P, TM>(smem + st, kk);
+      rdB.template issue_part<P, TN>(smem + st + A_BYTES, kk);
+      extra(P);
+    };
+    part(I<0>{}); part(I<1>{});
+    if constexpr (TM == 4) { part(I<2>{}); part(I<3>{}); }
+  };
+  auto nothing = [](int) {};
+
+  // Two 32-deep steps on K tiles t (stage r0) and t+1 (stage r1); r2 holds K tile t+2 and r4
+  // is free.  Each step is two 16-deep slices:
+  //   slice 0: MFMAs on fragments 0 | LDS reads of the stage's second slice
+  //   wait until the next K tile has landed, barrier: publishes it and retires this stage
   //   slice 1: MFMAs on fragments 1 | LDS reads of the next stage's first slice
-  //            | first half (operand A) of the refill of stage ST with K tile j + NSTAGE
-  // REFILL_B / REFILL_A say whether those refills exist; NEXT is false on the last step.
-  auto kstep = [&](int j, auto st_tag, auto refill_b_tag, auto refill_a_tag, auto wait_tag,
-                   auto next_tag) {
-    constexpr int ST = decltype(st_tag)::value;
-    constexpr bool REFILL_B = decltype(refill_b_tag)::value, REFILL_A = decltype(refill_a_tag)::value;
-    constexpr int WAIT = decltype(wait_tag)::value;
-    constexpr bool NEXT = decltype(next_tag)::value;
-    constexpr int PREV = (ST + NSTAGE - 1) % NSTAGE, NXT = (ST + 1) % NSTAGE;
-    // slice 0
-    rdA.issue(sA(ST), 1); rdB.issue(sB(ST), 1);
-    if constexpr (REFILL_B) {
-      if (ST != 0 || j > 0) ldB.issue(j - 1 + NSTAGE, lds0 + PREV * STAGE_BYTES + A_BYTES);
-    }
+  // REFILL: K tiles t+4 and t+5 are requested into r4 and r0 (r0 is free after the first
+  // barrier).  With a K-contiguous operand the two go as a pair, operand A during slice 1 of
+  // the first step and operand B during slice 0 of the second; when both operands are
+  // K-strided (whole cache lines anyway) they are spread over the four slices instead:
+  // A(t+4), B(t+4), A(t+5), B(t+5).
+  // W1 / W2: transfers that may still be in flight at the first / second barrier, i.e. all
+  // those requested after the K tile the barrier publishes.
+  // LAST: no K tile follows the second step.
+  constexpr bool SPREAD = AKS && BKS;
+  auto body = [&](int t, unsigned int r0, unsigned int r1, unsigned int r2, unsigned int r4,
+                  auto refill_tag, auto w1_tag, auto w2_tag, auto last_tag) {
+    constexpr bool REFILL = decltype(refill_tag)::value, LAST = decltype(last_tag)::value;
+    constexpr int W1 = decltype(w1_tag)::value, W2 = decltype(w2_tag)::value;
+    // ---- first step, slice 0
+    reads(r0, 1, [&](int p) {
+      if constexpr (REFILL && SPREAD) ldA.issue_one(t + 4, lds0 + r4, p);
+    });
     mfma_slice(0);
     rdA.finish(fa[1]); rdB.finish(fb[1]);
     interleave_hint<NM, NDSR, NPERM>();
-    if constexpr (NEXT) {
-      // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
-      __builtin_amdgcn_sched_barrier(0);
-      wait_vmcnt<WAIT>();
-      __syncthreads();
-      rdA.issue(sA(NXT), 0); rdB.issue(sB(NXT), 0);
-    }
-    // slice 1
-    if constexpr (REFILL_A) ldA.issue(j + NSTAGE, lds0 + ST * STAGE_BYTES);
+    // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<W1>();
+    __syncthreads();
+    // ---- first step, slice 1
+    reads(r1, 0, [&](int p) {
+      if constexpr (REFILL && SPREAD) ldB.issue_one(t + 4, lds0 + r4 + A_BYTES, p);
+      if constexpr (REFILL && !SPREAD) {
+        ldA.issue_one(t + 4, lds0 + r4, p);
+        ldA.issue_one(t + 5, lds0 + r0, p);
+      }
+    });
     mfma_slice(1);
-    if constexpr (NEXT) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
-    interleave_hint<NM, NEXT ? NDSR : 0, NEXT ? NPERM : 0>();
+    rdA.finish(fa[0]); rdB.finish(fb[0]);
+    interleave_hint<NM, NDSR, NPERM>();
+    // ---- second step, slice 0
+    reads(r1, 1, [&](int p) {
+      if constexpr (REFILL && SPREAD) ldA.issue_one(t + 5, lds0 + r0, p);
+      if constexpr (REFILL && !SPREAD) {
+        ldB.issue_one(t + 4, lds0 + r4 + A_BYTES, p);
+        ldB.issue_one(t + 5, lds0 + r0 + A_BYTES, p);
+      }
+    });
+    mfma_slice(0);
+    rdA.finish(fa[1]); rdB.finish(fb[1]);
+    interleave_hint<NM, NDSR, NPERM>();
+    if constexpr (!LAST) {
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt<W2>();
+      __syncthreads();
+      reads(r2, 0, [&](int p) {
+        if constexpr (REFILL && SPREAD) ldB.issue_one(t + 5, lds0 + r0 + A_BYTES, p);
+      });
+    }
+    // ---- second step, slice 1
+    mfma_slice(1);
+    if constexpr (!LAST) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
+    interleave_hint<NM, LAST ? 0 : NDSR, LAST ? 0 : NPERM>();
   };
   using T = std::true_type;
   using F = std::false_type;
@@ -469,26 +525,30 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
     // inserts no waits of its own inside the K loop.
     __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0), other counters unconstrained
     __syncthreads();
-    rdA.issue(sA(0), 0);
-    rdB.issue(sB(0), 0);
+    reads(0u, 0, nothing);
     rdA.finish(fa[0]);
     rdB.finish(fb[0]);
 
-    // Steady state: at the barrier of step j the transfers issued after K tile j+1 are the
-    // two younger K tiles = 2 * NDMA per thread.
-    int j = 0;
-    for (; j + 2 * NSTAGE <= KT; j += NSTAGE) {
-      kstep(j + 0, I<0>{}, T{}, T{}, I<2 * NDMA>{}, T{});
-      kstep(j + 1, I<1>{}, T{}, T{}, I<2 * NDMA>{}, T{});
-      kstep(j + 2, I<2>{}, T{}, T{}, I<2 * NDMA>{}, T{});
-      kstep(j + 3, I<3>{}, T{}, T{}, I<2 * NDMA>{}, T{});
+    // The ring rotates by two stages per body: r[x] = byte offset of the stage that holds
+    // (or will hold) K tile t + x.
+    unsigned int r0 = 0, r1 = STAGE_BYTES, r2 = 2 * STAGE_BYTES, r3 = 3 * STAGE_BYTES, r4 = 4 * STAGE_BYTES;
+    auto rotate = [&]() {
+      const unsigned int a0 = r0, a1 = r1;
+      r0 = r2; r1 = r3; r2 = r4; r3 = a0; r4 = a1;
+    };
+    // Transfers per thread in flight at a barrier of a body whose neighbours all refill,
+    // of the body after the last refill, and of the last body.
+    constexpr int STEADY = SPREAD ? 2 * NDMA + LoaderA::NCH : 2 * NDMA;
+    constexpr int DRAIN1 = 2 * NDMA, DRAIN2 = SPREAD ? NDMA : 0;
+    int t = 0;
+    for (; t + 4 < KT; t += 2) {           // K tiles t+4 and t+5 exist
+      body(t, r0, r1, r2, r4, T{}, I<STEADY>{}, I<STEADY>{}, F{});
+      rotate();
     }
-    // Last ring: nothing left to request except the second half of the refill begun by the
-    // step before; fewer and fewer transfers remain in flight.
-    kstep(j + 0, I<0>{}, T{}, F{}, I<2 * NDMA>{}, T{});
-    kstep(j + 1, I<1>{}, F{}, F{}, I<NDMA>{}, T{});
-    kstep(j + 2, I<2>{}, F{}, F{}, I<0>{}, T{});
-    kstep(j + 3, I<3>{}, F{}, F{}, I<0>{}, F{});
+    // Last two bodies: nothing left to request, fewer and fewer transfers in flight.
+    body(t, r0, r1, r2, r4, F{}, I<DRAIN1>{}, I<DRAIN2>{}, F{});
+    rotate();
+    body(t + 2, r0, r1, r2, r4, F{}, I<0>{}, I<0>{}, T{});
 
     const int next = logical + g.wg_per_xcd;
     const bool more = next < range_end;
@@ -574,7 +634,7 @@ int launch_layout(const GemmDesc& d, hipStream_t stream) {
 }  // namespace
 
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream) {
-  if (d.M % 128 || d.N % 128 || d.K % (NSTAGE * BK) || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0)
+  if (d.M % 128 || d.N % 128 || d.K % 128 || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0)
     return MLC_ERR_SHAPE;
   if ((d.lda | d.ldb | d.ldd | d.strideA | d.strideB | d.strideD) % 8) return MLC_ERR_SHAPE;
   if (d.C && ((d.ldc | d.strideC) % 8)) return MLC_ERR_SHAPE;
