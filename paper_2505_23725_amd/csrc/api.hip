@@ -153,8 +153,8 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
     if (rc != MLC_OK) return rc;
     // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
     g = GemmDesc{};
-    if (wide) {     // B' symmetric: read it K-strided like X, which has k as its slow index
-      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 1;
+    if (wide) {     // B' symmetric: read along rows (K-contiguous); X has k as its slow index
+      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
       g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = 1;
       g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
     } else {

@@ -45,6 +45,7 @@ constexpr int NSTAGE = 5;        // stages in the LDS ring
 constexpr int NPRE = 4;          // K tiles requested when an output tile starts
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;        // tile rows per group of the tile order
 
 struct GemmArgs {
   const bf16_t* A; long lda, strideA;
@@ -365,8 +366,15 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
       while (tm * (tm + 1) / 2 > rem) --tm;
       tn = rem - tm * (tm + 1) / 2;
     } else {
-      tm = rem / g.tiles_n;
-      tn = rem - tm * g.tiles_n;
+      // Groups of GROUP_M tile rows, column by column inside a group: the tiles an XCD works
+      // on at one time (consecutive indices) then form a block about as tall as it is wide
+      // and share few operand panels, which its L2 can hold.
+      const int per_group = GROUP_M * g.tiles_n;
+      const int grp = rem / per_group, r = rem - grp * per_group;
+      const int first_m = grp * GROUP_M;
+      const int rows = min(g.tiles_m - first_m, GROUP_M);
+      tn = r / rows;
+      tm = first_m + (r - tn * rows);
     }
     tc.m0 = tm * BM;
     tc.n0 = tn * BN;
@@ -628,6 +636,7 @@ int launch_layout(const GemmDesc& d, hipStream_t stream) {
   // mixed cases never arise.
   if (!d.a_kstrided && !d.b_kstrided) return launch_cfg<BM, BN, false, false>(d, stream);
   if (d.a_kstrided && d.b_kstrided) return launch_cfg<BM, BN, true, true>(d, stream);
+  if (!d.a_kstrided && d.b_kstrided) return launch_cfg<BM, BN, false, true>(d, stream);
   return MLC_ERR_UNSUPPORTED;
 }
 
