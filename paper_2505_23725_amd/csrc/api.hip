@@ -48,6 +48,10 @@ LaunchScope::~LaunchScope() {
 namespace {
 
 constexpr int64_t PAD = 128;               // GEMM tile granularity of the work-space layout
+// Row pitch of every work-space matrix = padded row length + 64 elements (one 128-byte
+// line): a pitch with a large power-of-two factor (5120 B, 6144 B, 10240 B ...) makes the
+// rows a workgroup fetches together fall on few L2 channels.
+constexpr int64_t PITCH_SKEW = 64;
 constexpr int64_t WS_ALIGN = 256;
 constexpr int MAX_NBLK = 1024;             // workgroups per matrix in the norm reduction
 constexpr int64_t MAX_CHUNK = 65535;       // gridDim.y limit
@@ -59,7 +63,7 @@ int check_shape(int64_t count, int64_t m, int64_t n) {
   const int64_t lim = (int64_t)1 << 30;    // per-dimension limit keeps int indexing valid
   if (m > lim || n > lim || count > lim) return MLC_ERR_SHAPE;
   const int64_t mp = round_up(m, PAD), np = round_up(n, PAD);
-  if (mp > ((int64_t)1 << 31) / np) {      // one padded matrix must stay below 2^31 elements
+  if (mp > ((int64_t)1 << 31) / (np + PITCH_SKEW)) {   // one padded matrix must stay below 2^31 elements
     return MLC_ERR_SHAPE;
   }
   if ((double)count * (double)mp * (double)np >= 4.0e18) return MLC_ERR_SHAPE;
@@ -69,6 +73,7 @@ int check_shape(int64_t count, int64_t m, int64_t n) {
 // Work-space layout for a chunk of c matrices:  X0 | X1 | A | B | scale | partials
 struct NsPlan {
   int64_t m, n, mp, np, sp;
+  int64_t ldx, lds;        // row pitch (elements) of X0/X1 and of A/B
   int nblk;
   size_t per_matrix;       // bytes that scale with the chunk size
   size_t x_bytes, s_bytes; // per matrix
@@ -79,13 +84,14 @@ NsPlan make_plan(int64_t m, int64_t n) {
   p.m = m; p.n = n;
   p.mp = round_up(m, PAD); p.np = round_up(n, PAD);
   p.sp = p.mp < p.np ? p.mp : p.np;
+  p.ldx = p.np + PITCH_SKEW; p.lds = p.sp + PITCH_SKEW;
   const int64_t items = p.mp * (p.np / 8);
   int64_t nblk = items / (256 * 4);
   if (nblk < 1) nblk = 1;
   if (nblk > MAX_NBLK) nblk = MAX_NBLK;
   p.nblk = (int)nblk;
-  p.x_bytes = (size_t)p.mp * p.np * 2;
-  p.s_bytes = (size_t)p.sp * p.sp * 2;
+  p.x_bytes = (size_t)p.mp * p.ldx * 2;
+  p.s_bytes = (size_t)p.sp * p.lds * 2;
   p.per_matrix = 2 * p.x_bytes + 2 * p.s_bytes + (size_t)WS_ALIGN /*scale slot*/ +
                  (size_t)round_up((int64_t)p.nblk * 4, WS_ALIGN);
   return p;
@@ -122,16 +128,16 @@ int64_t chunk_for(const NsPlan& p, size_t ws_bytes, int64_t count) {
 int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
                  float c, hipStream_t stream, int* result_buf) {
   const bool wide = p.mp <= p.np;
-  const int64_t xs = p.mp * p.np, ss = p.sp * p.sp;
+  const int64_t xs = p.mp * p.ldx, ss = p.sp * p.lds;
   int cur = 0;
   for (int it = 0; it < iters; ++it) {
     const bf16_t* X = w.X[cur];
     bf16_t* Xn = w.X[cur ^ 1];
     GemmDesc g{};
     // Gram matrix: A = X X^T (wide) or X^T X (tall)
-    g.A = X; g.lda = p.np; g.strideA = xs; g.a_kstrided = wide ? 0 : 1;
-    g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = wide ? 0 : 1;
-    g.D = w.A; g.ldd = p.sp; g.strideD = ss;
+    g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = wide ? 0 : 1;
+    g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = wide ? 0 : 1;
+    g.D = w.A; g.ldd = p.lds; g.strideD = ss;
     g.C = nullptr;
     g.M = (int)p.sp; g.N = (int)p.sp; g.K = (int)(wide ? p.np : p.mp); g.batch = (int)chunk;
     g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
@@ -142,10 +148,10 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
     // Polynomial: B' = c A A + b A + a I.  A is symmetric, so either operand may be read
     // along rows or along columns; the K-contiguous LDS path is the faster one.
     g = GemmDesc{};
-    g.A = w.A; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
-    g.B = w.A; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
-    g.D = w.B; g.ldd = p.sp; g.strideD = ss;
-    g.C = w.A; g.ldc = p.sp; g.strideC = ss;
+    g.A = w.A; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
+    g.B = w.A; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
+    g.D = w.B; g.ldd = p.lds; g.strideD = ss;
+    g.C = w.A; g.ldc = p.lds; g.strideC = ss;
     g.M = g.N = g.K = (int)p.sp; g.batch = (int)chunk;
     g.alpha = c; g.beta = b; g.gamma = a;
     g.symmetric = 1;
@@ -154,15 +160,15 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
     // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
     g = GemmDesc{};
     if (wide) {     // B' symmetric: read along rows (K-contiguous); X has k as its slow index
-      g.A = w.B; g.lda = p.sp; g.strideA = ss; g.a_kstrided = 0;
-      g.B = X; g.ldb = p.np; g.strideB = xs; g.b_kstrided = 1;
+      g.A = w.B; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
+      g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = 1;
       g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
     } else {
-      g.A = X; g.lda = p.np; g.strideA = xs; g.a_kstrided = 0;
-      g.B = w.B; g.ldb = p.sp; g.strideB = ss; g.b_kstrided = 0;
+      g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = 0;
+      g.B = w.B; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
       g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.np;
     }
-    g.D = Xn; g.ldd = p.np; g.strideD = xs;
+    g.D = Xn; g.ldd = p.ldx; g.strideD = xs;
     g.C = nullptr; g.batch = (int)chunk;
     g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
     g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 1;
@@ -237,7 +243,7 @@ int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_
     const NsBuffers w = carve(p, workspace, chunk);
     const unsigned char* src = (const unsigned char*)in + (size_t)c0 * m * n * es;
     unsigned char* dst = (unsigned char*)out + (size_t)c0 * m * n * es;
-    rc = launch_ns_load(src, io_dtype, w.X[0], w.partials, p.nblk, cc, m, n, p.mp, p.np, stream);
+    rc = launch_ns_load(src, io_dtype, w.X[0], w.partials, p.nblk, cc, m, n, p.mp, p.np, p.ldx, stream);
     if (rc != MLC_OK) return rc;
     rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, eps, stream);
     if (rc != MLC_OK) return rc;
@@ -245,7 +251,7 @@ int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_
     rc = run_ns_chunk(p, w, cc, iters, a, b, c, stream, &res);
     if (rc != MLC_OK) return rc;
     rc = launch_ns_store(w.X[res], iters == 0 ? w.scale : nullptr, dst, io_dtype, cc, m, n, p.mp,
-                         p.np, stream);
+                         p.ldx, stream);
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;
@@ -308,7 +314,7 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
       unsigned char* param = (unsigned char*)g.param + c0 * mat * elem_size(g.param_dtype);
       float* mom = g.momentum + c0 * mat;
       rc = launch_momentum(grad, g.grad_dtype, mom, w.X[0], w.partials, p.nblk, cc, g.m, g.n, p.mp,
-                           p.np, hp->beta, hp->nesterov, stream);
+                           p.np, p.ldx, hp->beta, hp->nesterov, stream);
       if (rc != MLC_OK) return rc;
       rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, hp->ns_eps, stream);
       if (rc != MLC_OK) return rc;
@@ -316,7 +322,7 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
       rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, stream, &res);
       if (rc != MLC_OK) return rc;
       rc = launch_param_update(param, g.param_dtype, w.X[res], hp->ns_iters == 0 ? w.scale : nullptr,
-                               cc, g.m, g.n, p.mp, p.np, decay_factor, hp->eta * g.lr_scale, stream);
+                               cc, g.m, g.n, p.mp, p.ldx, decay_factor, hp->eta * g.lr_scale, stream);
       if (rc != MLC_OK) return rc;
     }
   }

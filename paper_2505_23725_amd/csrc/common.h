@@ -75,17 +75,17 @@ int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
 // ---- elementwise kernels of the inner step (inner_elementwise.hip) ----------------
 int launch_momentum(const void* grad, int grad_dtype, float* mom, bf16_t* U, float* partials,
                     int nblk, int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
-                    float beta, int nesterov, hipStream_t stream);
+                    int64_t ldx, float beta, int nesterov, hipStream_t stream);
 int launch_ns_load(const void* in, int dtype, bf16_t* U, float* partials, int nblk,
-                   int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
+                   int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np, int64_t ldx,
                    hipStream_t stream);
 int launch_norm_finalize(const float* partials, int nblk, float* scale, int64_t count,
                          float eps, hipStream_t stream);
 int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale,
-                        int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
+                        int64_t count, int64_t m, int64_t n, int64_t mp, int64_t ldx,
                         float decay_factor, float step, hipStream_t stream);
 int launch_ns_store(const bf16_t* X, const float* oscale, void* out, int dtype, int64_t count,
-                    int64_t m, int64_t n, int64_t mp, int64_t np, hipStream_t stream);
+                    int64_t m, int64_t n, int64_t mp, int64_t ldx, hipStream_t stream);
 
 // ---- outer step kernels (outer.hip) ----------------------------------------------
 struct WorkerPtrs { void* p[MLC_MAX_WORKERS]; };

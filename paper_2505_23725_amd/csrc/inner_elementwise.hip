@@ -84,12 +84,12 @@ __device__ __forceinline__ float block_sum(float v) {
 template <typename GT, bool WITH_MOM, bool VEC>
 __global__ __launch_bounds__(EW_THREADS) void muon_momentum_kernel(
     const GT* __restrict__ grad, float* __restrict__ mom, bf16_t* __restrict__ U,
-    float* __restrict__ partials, int m, int n, int mp, int np, float beta, int nesterov) {
+    float* __restrict__ partials, int m, int n, int mp, int np, int ldx, float beta, int nesterov) {
   const int b = blockIdx.y;
   const long mat = (long)b * m * n;
   const GT* g = grad + mat;
   float* mo = WITH_MOM ? mom + mat : nullptr;
-  bf16_t* u = U + (long)b * mp * np;
+  bf16_t* u = U + (long)b * mp * ldx;
   const int vec_per_row = np / 8;
   const long items = (long)mp * vec_per_row;
   float ss = 0.f;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(EW_THREADS) void muon_momentum_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j) ss += uv[j] * uv[j];
     }
-    Vec8<bf16_t>::store(u + (long)row * np + col, uv);
+    Vec8<bf16_t>::store(u + (long)row * ldx + col, uv);
   }
   const float tot = block_sum(ss);
   if (threadIdx.x == 0) partials[(long)b * gridDim.x + blockIdx.x] = tot;
@@ -156,10 +156,10 @@ __global__ __launch_bounds__(EW_THREADS) void muon_norm_kernel(const float* __re
 template <typename WT, bool VEC>
 __global__ __launch_bounds__(EW_THREADS) void muon_update_kernel(
     WT* __restrict__ W, const bf16_t* __restrict__ O, const float* __restrict__ oscale, int m, int n,
-    int mp, int np, float decay_factor, float step) {
+    int mp, int ldx, float decay_factor, float step) {
   const int b = blockIdx.y;
   WT* w = W + (long)b * m * n;
-  const bf16_t* o = O + (long)b * mp * np;
+  const bf16_t* o = O + (long)b * mp * ldx;
   const float st = oscale ? step * oscale[b] : step;
   const int vec_per_row = (n + 7) / 8;
   const long items = (long)m * vec_per_row;
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(EW_THREADS) void muon_update_kernel(
     const int col = (int)(it - (long)row * vec_per_row) * 8;
     const long off = (long)row * n + col;
     float ov[8], wv[8];
-    Vec8<bf16_t>::load_nt(o + (long)row * np + col, ov);   // padded layout: always in bounds
+    Vec8<bf16_t>::load_nt(o + (long)row * ldx + col, ov);   // padded layout: always in bounds
     if (VEC) {
       Vec8<WT>::load_nt(w + off, wv);
 #pragma unroll
@@ -190,10 +190,10 @@ __global__ __launch_bounds__(EW_THREADS) void muon_update_kernel(
 template <typename OT, bool VEC>
 __global__ __launch_bounds__(EW_THREADS) void ns_store_kernel(
     const bf16_t* __restrict__ X, const float* __restrict__ oscale, OT* __restrict__ out, int m,
-    int n, int mp, int np) {
+    int n, int mp, int ldx) {
   const int b = blockIdx.y;
   OT* o = out + (long)b * m * n;
-  const bf16_t* x = X + (long)b * mp * np;
+  const bf16_t* x = X + (long)b * mp * ldx;
   const float sc = oscale ? oscale[b] : 1.0f;
   const int vec_per_row = (n + 7) / 8;
   const long items = (long)m * vec_per_row;
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(EW_THREADS) void ns_store_kernel(
     const int col = (int)(it - (long)row * vec_per_row) * 8;
     const long off = (long)row * n + col;
     float xv[8];
-    Vec8<bf16_t>::load(x + (long)row * np + col, xv);
+    Vec8<bf16_t>::load(x + (long)row * ldx + col, xv);
 #pragma unroll
     for (int j = 0; j < 8; ++j) xv[j] *= sc;
     if (VEC) {
@@ -227,18 +227,18 @@ int grid_blocks(long items, int cap) {
 
 template <typename GT, bool WITH_MOM>
 int launch_momentum_t(const GT* grad, float* mom, bf16_t* U, float* partials, int nblk,
-                      int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np, float beta,
-                      int nesterov, hipStream_t stream, int family) {
+                      int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np, int64_t ldx,
+                      float beta, int nesterov, hipStream_t stream, int family) {
   const dim3 grid(nblk, (unsigned)count), block(EW_THREADS);
   const double elems = (double)count * m * n;
   const double bytes = elems * (sizeof(GT) + (WITH_MOM ? 8 : 0)) + (double)count * mp * np * 2;
   LaunchScope scope(family, stream, 0.0, bytes);
   if (n % 8 == 0)
     hipLaunchKernelGGL((muon_momentum_kernel<GT, WITH_MOM, true>), grid, block, 0, stream, grad, mom,
-                       U, partials, (int)m, (int)n, (int)mp, (int)np, beta, nesterov);
+                       U, partials, (int)m, (int)n, (int)mp, (int)np, (int)ldx, beta, nesterov);
   else
     hipLaunchKernelGGL((muon_momentum_kernel<GT, WITH_MOM, false>), grid, block, 0, stream, grad, mom,
-                       U, partials, (int)m, (int)n, (int)mp, (int)np, beta, nesterov);
+                       U, partials, (int)m, (int)n, (int)mp, (int)np, (int)ldx, beta, nesterov);
   return check_launch();
 }
 
@@ -246,21 +246,21 @@ int launch_momentum_t(const GT* grad, float* mom, bf16_t* U, float* partials, in
 
 int launch_momentum(const void* grad, int grad_dtype, float* mom, bf16_t* U, float* partials,
                     int nblk, int64_t count, int64_t m, int64_t n, int64_t mp, int64_t np,
-                    float beta, int nesterov, hipStream_t stream) {
+                    int64_t ldx, float beta, int nesterov, hipStream_t stream) {
   if (grad_dtype == MLC_F32)
     return launch_momentum_t<float, true>((const float*)grad, mom, U, partials, nblk, count, m, n,
-                                          mp, np, beta, nesterov, stream, MLC_KERNEL_MOMENTUM);
+                                          mp, np, ldx, beta, nesterov, stream, MLC_KERNEL_MOMENTUM);
   return launch_momentum_t<bf16_t, true>((const bf16_t*)grad, mom, U, partials, nblk, count, m, n,
-                                         mp, np, beta, nesterov, stream, MLC_KERNEL_MOMENTUM);
+                                         mp, np, ldx, beta, nesterov, stream, MLC_KERNEL_MOMENTUM);
 }
 
 int launch_ns_load(const void* in, int dtype, bf16_t* U, float* partials, int nblk, int64_t count,
-                   int64_t m, int64_t n, int64_t mp, int64_t np, hipStream_t stream) {
+                   int64_t m, int64_t n, int64_t mp, int64_t np, int64_t ldx, hipStream_t stream) {
   if (dtype == MLC_F32)
     return launch_momentum_t<float, false>((const float*)in, nullptr, U, partials, nblk, count, m,
-                                           n, mp, np, 0.f, 0, stream, MLC_KERNEL_CONVERT);
+                                           n, mp, np, ldx, 0.f, 0, stream, MLC_KERNEL_CONVERT);
   return launch_momentum_t<bf16_t, false>((const bf16_t*)in, nullptr, U, partials, nblk, count, m,
-                                          n, mp, np, 0.f, 0, stream, MLC_KERNEL_CONVERT);
+                                          n, mp, np, ldx, 0.f, 0, stream, MLC_KERNEL_CONVERT);
 }
 
 int launch_norm_finalize(const float* partials, int nblk, float* scale, int64_t count, float eps,
@@ -272,7 +272,7 @@ int launch_norm_finalize(const float* partials, int nblk, float* scale, int64_t 
 }
 
 int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale, int64_t count,
-                        int64_t m, int64_t n, int64_t mp, int64_t np, float decay_factor, float step,
+                        int64_t m, int64_t n, int64_t mp, int64_t ldx, float decay_factor, float step,
                         hipStream_t stream) {
   const long items = m * ((n + 7) / 8);
   const dim3 grid(grid_blocks(items, 2048), (unsigned)count), block(EW_THREADS);
@@ -282,7 +282,7 @@ int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale
   const bool vec = n % 8 == 0;
 #define MLC_UPD(WT, V)                                                                          \
   hipLaunchKernelGGL((muon_update_kernel<WT, V>), grid, block, 0, stream, (WT*)W, O, oscale, (int)m, \
-                     (int)n, (int)mp, (int)np, decay_factor, step)
+                     (int)n, (int)mp, (int)ldx, decay_factor, step)
   if (dtype == MLC_F32) { if (vec) MLC_UPD(float, true); else MLC_UPD(float, false); }
   else { if (vec) MLC_UPD(bf16_t, true); else MLC_UPD(bf16_t, false); }
 #undef MLC_UPD
@@ -290,7 +290,7 @@ int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale
 }
 
 int launch_ns_store(const bf16_t* X, const float* oscale, void* out, int dtype, int64_t count,
-                    int64_t m, int64_t n, int64_t mp, int64_t np, hipStream_t stream) {
+                    int64_t m, int64_t n, int64_t mp, int64_t ldx, hipStream_t stream) {
   const long items = m * ((n + 7) / 8);
   const dim3 grid(grid_blocks(items, 2048), (unsigned)count), block(EW_THREADS);
   const double elems = (double)count * m * n;
@@ -298,7 +298,7 @@ int launch_ns_store(const bf16_t* X, const float* oscale, void* out, int dtype, 
   const bool vec = n % 8 == 0;
 #define MLC_ST(OT, V)                                                                             \
   hipLaunchKernelGGL((ns_store_kernel<OT, V>), grid, block, 0, stream, X, oscale, (OT*)out, (int)m, \
-                     (int)n, (int)mp, (int)np)
+                     (int)n, (int)mp, (int)ldx)
   if (dtype == MLC_F32) { if (vec) MLC_ST(float, true); else MLC_ST(float, false); }
   else { if (vec) MLC_ST(bf16_t, true); else MLC_ST(bf16_t, false); }
 #undef MLC_ST

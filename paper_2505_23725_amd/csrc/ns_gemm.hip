@@ -45,7 +45,7 @@ constexpr int NSTAGE = 5;        // stages in the LDS ring
 constexpr int NPRE = 4;          // K tiles requested when an output tile starts
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;        // tile rows per group of the tile order
+constexpr int GROUP_M = 8;        // most tile rows per group of the tile order
 
 struct GemmArgs {
   const bf16_t* A; long lda, strideA;
@@ -54,6 +54,7 @@ struct GemmArgs {
   const bf16_t* C; long ldc, strideC;
   int K, batch;
   int tiles_m, tiles_n, tiles_per_mat, total_tiles, tiles_per_xcd, wg_per_xcd;
+  int group_m;                    // tile rows per group of the tile order
   int symmetric;
   float alpha, beta, gamma;
   const float* bscale; int bscale_pow;
@@ -366,13 +367,13 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
       while (tm * (tm + 1) / 2 > rem) --tm;
       tn = rem - tm * (tm + 1) / 2;
     } else {
-      // Groups of GROUP_M tile rows, column by column inside a group: the tiles an XCD works
+      // Groups of group_m tile rows, column by column inside a group: the tiles an XCD works
       // on at one time (consecutive indices) then form a block about as tall as it is wide
       // and share few operand panels, which its L2 can hold.
-      const int per_group = GROUP_M * g.tiles_n;
+      const int per_group = g.group_m * g.tiles_n;
       const int grp = rem / per_group, r = rem - grp * per_group;
-      const int first_m = grp * GROUP_M;
-      const int rows = min(g.tiles_m - first_m, GROUP_M);
+      const int first_m = grp * g.group_m;
+      const int rows = min(g.tiles_m - first_m, g.group_m);
       tn = r / rows;
       tm = first_m + (r - tn * rows);
     }
@@ -603,6 +604,10 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   g.K = d.K; g.batch = d.batch;
   g.tiles_m = d.M / BM; g.tiles_n = d.N / BN;
   g.symmetric = d.symmetric ? 1 : 0;
+  {   // equal groups of at most GROUP_M tile rows (10 rows -> 5 + 5, not 8 + 2)
+    const int ngroups = (g.tiles_m + GROUP_M - 1) / GROUP_M;
+    g.group_m = (g.tiles_m + ngroups - 1) / ngroups;
+  }
   if (g.symmetric && (BM != BN || d.M != d.N)) return MLC_ERR_SHAPE;
   g.tiles_per_mat = g.symmetric ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
   const long total = (long)g.tiles_per_mat * d.batch;

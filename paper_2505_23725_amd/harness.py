@@ -46,18 +46,18 @@ class MulocoJob:
         self.mom: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
         self.grad: List[List[torch.Tensor]] = [[] for _ in range(self.K)]
         for gi, shp in enumerate(self.shapes):
-            init = self._draw(shp, S.PARAM_STD, 100 + gi, self.pdtype)   # theta^(0), worker dtype
-            self.theta_g.append(init.to(torch.float32))
+            self.theta_g.append(torch.empty(shp, dtype=torch.float32, device=self.device))
             self.u.append(torch.zeros(shp, dtype=torch.float32, device=self.device))
             self.W.append(torch.empty((self.K,) + tuple(shp), dtype=self.pdtype, device=self.device))
             self.M.append(torch.zeros((self.K,) + tuple(shp), dtype=torch.float32, device=self.device))
             self.G.append(torch.zeros((self.K,) + tuple(shp), dtype=self.gdtype, device=self.device))
+            # theta^(0) in the worker dtype, the same for the global copy and every replica
+            self._fill([self.theta_g[gi]] + [self.W[gi][k] for k in range(self.K)], shp,
+                       S.PARAM_STD, 100 + gi, self.pdtype)
             for k in range(self.K):
-                self.W[gi][k].copy_(init)
                 self.workers[k].append(self.W[gi][k])
                 self.mom[k].append(self.M[gi][k])
                 self.grad[k].append(self.G[gi][k])
-            del init
         self.codes = self.scales = None
         if with_quant:
             self.codes = [[torch.empty((c * m, n // 2), dtype=torch.uint8, device=self.device)
@@ -74,6 +74,31 @@ class MulocoJob:
     def _draw(self, shape, std, stream, dtype):
         return S.normal(shape, std, self.seed, stream, device=self.gen_dev, dtype=dtype).to(self.device)
 
+    # Largest number of elements drawn at once on the device: the fp32 temporary of a whole
+    # 15B-scale group would not fit beside the resident state.
+    DEVICE_DRAW_ELEMS = 1 << 28
+
+    def _fill(self, dsts, shape, std, stream, dtype) -> None:
+        """dst.copy_(std * N(0,1) rounded to `dtype`) for every dst.  Drawn on the CPU the
+        tensor is one draw of `stream` (what a parity test reproduces on the host); drawn on
+        the device it is made of slices along the first dimension, one sub-stream each."""
+        count = shape[0]
+        per = 1
+        for v in shape[1:]:
+            per *= v
+        step = count if self.gen_dev == "cpu" else max(1, self.DEVICE_DRAW_ELEMS // per)
+        if step >= count:
+            x = self._draw(shape, std, stream, dtype)
+            for d in dsts:
+                d.copy_(x)
+            return
+        for i, c0 in enumerate(range(0, count, step)):
+            c1 = min(count, c0 + step)
+            x = self._draw((c1 - c0,) + tuple(shape[1:]), std, stream * 65_536 + i + 1_000_000, dtype)
+            for d in dsts:
+                d[c0:c1].copy_(x)
+            del x
+
     def grad_stream(self, k: int, step: int, gi: int) -> int:
         return 10_000 + (step * 64 + k) * 8 + gi
 
@@ -81,15 +106,20 @@ class MulocoJob:
         """Fresh i.i.d. gradients for every replica: g ~ 1e-3 N(0,1), keyed by (k, step, group)."""
         for k in range(self.K):
             for gi, shp in enumerate(self.shapes):
-                self.grad[k][gi].copy_(self._draw(shp, S.GRAD_STD, self.grad_stream(k, step, gi), self.gdtype))
+                self._fill([self.grad[k][gi]], shp, S.GRAD_STD, self.grad_stream(k, step, gi), self.gdtype)
 
     def displace_workers(self, std: float = S.DELTA_STD) -> None:
         """theta_k = theta_g - Delta_k with Delta_k ~ std N(0,1): stands in for H inner steps
         when only the outer step is exercised."""
         for k in range(self.K):
             for gi, shp in enumerate(self.shapes):
-                delta = self._draw(shp, std, 5_000 + k * 8 + gi, torch.float32)
-                self.workers[k][gi].copy_((self.theta_g[gi] - delta).to(self.pdtype))
+                # the replica first receives Delta_k, then theta_g - Delta_k in place
+                w = self.workers[k][gi]
+                self._fill([w], shp, std, 5_000 + k * 8 + gi, torch.float32)
+                step = max(1, self.DEVICE_DRAW_ELEMS // (shp[1] * shp[2]))
+                for c0 in range(0, shp[0], step):
+                    c1 = min(shp[0], c0 + step)
+                    w[c0:c1].copy_(self.theta_g[gi][c0:c1] - w[c0:c1].to(torch.float32))
 
     # -- descriptors --------------------------------------------------------------------
     @staticmethod

@@ -40,12 +40,14 @@ def test_workspace_sizes():
     one = mlc.newton_schulz_workspace_min_bytes(2048, 2048)
     # two X buffers + Gram + polynomial, bf16, plus small per-matrix slots
     assert one >= 4 * 2048 * 2048 * 2
-    assert one < 4 * 2048 * 2048 * 2 + 16384
+    # ... and a row pitch skewed by one 128-byte line per row of each of the four buffers
+    assert one < 4 * 2048 * (2048 + 64) * 2 + 16384
     assert mlc.newton_schulz_workspace_bytes(96, 2048, 2048) == 96 * one
     # padding to the 128 tile granularity
     assert mlc.newton_schulz_workspace_min_bytes(100, 130) == mlc.newton_schulz_workspace_min_bytes(128, 256)
-    # tall and wide need the same space
-    assert mlc.newton_schulz_workspace_min_bytes(512, 128) == mlc.newton_schulz_workspace_min_bytes(128, 512)
+    # tall and wide differ only by the pitch skew of their rows
+    tall, wide = mlc.newton_schulz_workspace_min_bytes(512, 128), mlc.newton_schulz_workspace_min_bytes(128, 512)
+    assert abs(tall - wide) == 2 * (512 - 128) * 64 * 2
     assert mlc.newton_schulz_workspace_bytes(0, 8, 8) == 0
     assert mlc.newton_schulz_workspace_min_bytes(-1, 8) == 0
 
