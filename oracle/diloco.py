@@ -17,7 +17,14 @@ with Nesterov momentum) and Algorithm 2's "compress parameter delta" branch.  Re
       q_j   = clamp(rint(delta_j / scale), -qmax, qmax), ties to even; 0 if amax == 0
       code  = q_j + 2^(bits-1); two 4-bit codes per byte, even column in the low nibble
       dequantised value = float(q_j) * scale         (one fp32 multiplication)
-  One quantisation per worker, before the average.
+  One quantisation per worker, before the average.  bits may be 8, 4 or 2: one, two or four
+  codes per byte, the code of the lowest column in the lowest bits.
+* Error feedback (Sec. 2 "Compressed Communication", Algorithm 2, EF branch): the residual
+  E_k is kept in fp32 and the stage that feeds the quantiser is again fixed in fp32,
+      e     = fl32(fl32(beta * E_k) + delta)         (a product, then a sum; not fused)
+      (q, scale) = quantise(e) row-wise as above;  communicated value = float(q) * scale
+      E_k  <- fl32(e - float(q) * scale)
+  and the communicated values are averaged in place of the deltas.
 """
 import numpy as np
 
@@ -47,23 +54,71 @@ def outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov=True):
     return theta, u
 
 
+def quantize_values_rowwise(values_f32, bits=4):
+    """Row-wise linear quantisation of a 2-D float32 array, in fp32 as specified above.
+
+    Returns (q int8 [rows, n], scale float32 [rows])."""
+    v = np.asarray(values_f32, dtype=np.float32)
+    assert v.ndim == 2
+    qmax = np.float32(2 ** (bits - 1) - 1)
+    amax = np.max(np.abs(v), axis=1).astype(np.float32)
+    scale = (amax / qmax).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    ratio = (v / safe[:, None]).astype(np.float32)
+    q = np.clip(np.rint(ratio), -qmax, qmax)
+    q = np.where(scale[:, None] > 0, q, 0.0).astype(np.int8)
+    return q, scale
+
+
 def quantize_rowwise(theta_g_f32, theta_k_f32, bits=4):
-    """Row-wise linear quantisation of theta_g - theta_k, in fp32 as specified above.
+    """Row-wise linear quantisation of theta_g - theta_k (one fp32 subtraction first).
 
     Inputs are 2-D float32 arrays [rows, n] holding the stored values exactly.
     Returns (q int8 [rows, n], scale float32 [rows])."""
     tg = np.asarray(theta_g_f32, dtype=np.float32)
     tk = np.asarray(theta_k_f32, dtype=np.float32)
     assert tg.ndim == 2 and tg.shape == tk.shape
-    qmax = np.float32(2 ** (bits - 1) - 1)
+    return quantize_values_rowwise((tg - tk).astype(np.float32), bits)
+
+
+def error_feedback_compress(theta_g_f32, theta_k_f32, residual_f32, beta, bits=4):
+    """Algorithm 2, EF branch, for one worker: E <- beta E + Delta; Delta~ = C(E); E <- E - Delta~.
+
+    Returns (q, scale, new residual float32); the communicated value is dequantize_rowwise(q, scale)."""
+    tg = np.asarray(theta_g_f32, dtype=np.float32)
+    tk = np.asarray(theta_k_f32, dtype=np.float32)
+    E = np.asarray(residual_f32, dtype=np.float32)
+    assert tg.ndim == 2 and tg.shape == tk.shape == E.shape
     delta = (tg - tk).astype(np.float32)
-    amax = np.max(np.abs(delta), axis=1).astype(np.float32)
-    scale = (amax / qmax).astype(np.float32)
-    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
-    ratio = (delta / safe[:, None]).astype(np.float32)
-    q = np.clip(np.rint(ratio), -qmax, qmax)
-    q = np.where(scale[:, None] > 0, q, 0.0).astype(np.int8)
-    return q, scale
+    e = ((np.float32(beta) * E).astype(np.float32) + delta).astype(np.float32)
+    q, scale = quantize_values_rowwise(e, bits)
+    sent = dequantize_rowwise(q, scale)
+    return q, scale, (e - sent).astype(np.float32)
+
+
+def pack_codes(q, bits):
+    """Signed levels -> packed bytes: code = q + 2^(bits-1), 8 / bits codes per byte, the
+    lowest column of a byte's group in its lowest bits."""
+    assert bits in (2, 4, 8)
+    per = 8 // bits
+    q = np.asarray(q, dtype=np.int16)
+    assert q.shape[-1] % per == 0
+    c = (q + 2 ** (bits - 1)).astype(np.uint8)
+    out = np.zeros(q.shape[:-1] + (q.shape[-1] // per,), dtype=np.uint8)
+    for j in range(per):
+        out |= (c[..., j::per] << (bits * j)).astype(np.uint8)
+    return out
+
+
+def unpack_codes(packed, bits):
+    assert bits in (2, 4, 8)
+    per = 8 // bits
+    p = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * per,), dtype=np.int16)
+    mask = (1 << bits) - 1
+    for j in range(per):
+        out[..., j::per] = ((p >> (bits * j)) & mask).astype(np.int16) - 2 ** (bits - 1)
+    return out.astype(np.int8)
 
 
 def pack_codes4(q):
@@ -87,24 +142,34 @@ def dequantize_rowwise(q, scale):
     return (np.asarray(q, np.float32) * np.asarray(scale, np.float32)[:, None]).astype(np.float32)
 
 
-def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0):
+def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0,
+               residuals=None, ef_beta=1.0):
     """One outer step on one 2-D tensor [rows, n].
 
     theta_g, thetas[k]: stored values (float64 holding fp32/bf16-representable numbers).
-    Returns dict with theta (new global), u, psi, and for the quantised path the
-    per-worker levels q[k] and scales[k]."""
+    residuals: per-worker EF accumulators E_k (float32) or None for no error feedback.
+    Returns dict with theta (new global), u, psi, for the quantised path the per-worker
+    levels q[k] and scales[k], and with error feedback the new residuals."""
     theta_g = np.asarray(theta_g, np.float64)
     out = {}
     deltas = []
     if quant_bits:
         out["q"], out["scales"] = [], []
-        for th in thetas:
-            q, s = quantize_rowwise(theta_g.astype(np.float32),
-                                    np.asarray(th, np.float64).astype(np.float32), quant_bits)
+        if residuals is not None:
+            out["residuals"] = []
+        for k, th in enumerate(thetas):
+            tg32 = theta_g.astype(np.float32)
+            tk32 = np.asarray(th, np.float64).astype(np.float32)
+            if residuals is not None:
+                q, s, e_new = error_feedback_compress(tg32, tk32, residuals[k], ef_beta, quant_bits)
+                out["residuals"].append(e_new)
+            else:
+                q, s = quantize_rowwise(tg32, tk32, quant_bits)
             out["q"].append(q)
             out["scales"].append(s)
             deltas.append(dequantize_rowwise(q, s).astype(np.float64))
     else:
+        assert residuals is None, "error feedback needs a compressor"
         for th in thetas:
             deltas.append(pseudogradient(theta_g, th))
     psi = average(deltas)
