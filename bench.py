@@ -142,6 +142,41 @@ def main() -> int:
     quant_alone = {"ms": q["total_ms"] / 3, "GBps": q["bytes"] / (q["total_ms"] * 1e-3) * 1e-9 if q["total_ms"] > 0 else 0.0}
     quant_alone["frac_hbm"] = quant_alone["GBps"] / PEAK_HBM_GBS
 
+    # Also outside the timed region: the quantised outer step over the whole model with error
+    # feedback (4 bit) and in its 8- and 2-bit forms, when their extra buffers fit in memory.
+    variants = {}
+    free_bytes = torch.cuda.mem_get_info()[0]
+    n_elems = sum(c * m * n for (c, m, n) in job.shapes)
+    for name, bits, ef in (("4bit_error_feedback", 4, True), ("8bit", 8, False), ("2bit", 2, False)):
+        need = job.K * n_elems * (bits / 8 + (4 if ef else 0)) + (1 << 30)
+        if need > free_bytes:
+            variants[name] = None
+            continue
+        groups = []
+        for gi, (c, m, n) in enumerate(job.shapes):
+            g = mlc.OuterGroup([job.workers[k][gi] for k in range(job.K)], job.theta_g[gi], job.u[gi])
+            g.codes = [torch.empty((c * m, n * bits // 8), dtype=torch.uint8, device="cuda:0") for _ in range(job.K)]
+            g.scales = [job.scales[k][gi] for k in range(job.K)]
+            if ef:
+                g.residuals = [torch.zeros((c, m, n), dtype=torch.float32, device="cuda:0") for _ in range(job.K)]
+            groups.append(g)
+        hpv = job.outer_hparams(quant_bits=bits, error_feedback=ef, ef_beta=0.9)
+        mlc.muloco_outer_step(groups, hpv)              # warm-up
+        torch.cuda.synchronize()
+        mlc.muloco_timing_enable(True)
+        mlc.muloco_timing_read()
+        for _ in range(2):
+            mlc.muloco_outer_step(groups, hpv)
+        torch.cuda.synchronize()
+        tv = mlc.muloco_timing_read()
+        mlc.muloco_timing_enable(False)
+        ms = sum(tv[k]["total_ms"] for k in ("quantize", "dequant_outer"))
+        nbytes = sum(tv[k]["bytes"] for k in ("quantize", "dequant_outer"))
+        gbs = nbytes / (ms * 1e-3) * 1e-9 if ms > 0 else 0.0
+        variants[name] = {"ms": ms / 2, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        del groups
+        torch.cuda.empty_cache()
+
     ms_per_step = wall * 1e3 / args.steps
     gemm = timing["ns_gemm"]
     ns_tflops = gemm["flops"] / (gemm["total_ms"] * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
@@ -161,6 +196,7 @@ def main() -> int:
         "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
         "quantize_outer_fused": fam("dequant_outer"),
         "quantize_standalone_whole_model": quant_alone,
+        "quantised_outer_step_whole_model_variants": variants,
         "nominal_ns_tflops_equivalent": None,
     }
     nominal = job.ns_flops() * job.K

@@ -132,12 +132,22 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     theta_g<- theta_g - u                          (nesterov = 0)
  *     theta_k<- theta_g for every k                  (write_back = 1)
  *
- * Quantiser (quant_bits = 4): row-wise linear, symmetric, defined in IEEE fp32 so that
- * codes are reproducible bit for bit.  For each row (length n) of each matrix:
- *     delta = fl32(theta_g) - fl32(theta_k);  amax = max |delta|;  scale = amax / 7
- *     q = clamp(rint(delta / scale), -7, 7) (ties to even), q = 0 when amax = 0
- *     code = q + 8 in [1, 15]; byte i of a row = code[2i] | code[2i+1] << 4
+ * Quantiser (quant_bits = 2, 4 or 8): row-wise linear, symmetric, defined in IEEE fp32 so
+ * that codes are reproducible bit for bit.  With qmax = 2^(bits-1) - 1 (1, 7, 127), for each
+ * row (length n) of each matrix:
+ *     delta = fl32(theta_g) - fl32(theta_k);  amax = max |delta|;  scale = amax / qmax
+ *     q = clamp(rint(delta / scale), -qmax, qmax) (ties to even), q = 0 when amax = 0
+ *     code = q + 2^(bits-1); a byte holds 8 / bits codes, the lowest column in the lowest
+ *     bits (4 bit: byte i of a row = code[2i] | code[2i+1] << 4)
  *     dequantised value = (float)q * scale
+ * n must be a multiple of 8 / bits.
+ *
+ * Error feedback (paper Sec. 2 "Compressed Communication"; Algorithm 2, EF branch), with
+ * error_feedback = 1 and one fp32 residual E_k per worker, also fixed in fp32:
+ *     e   = fl32(fl32(ef_beta * E_k) + delta)      (product, then sum; not fused)
+ *     the row of e is quantised as above and its dequantised values are what is averaged
+ *     E_k <- fl32(e - (float)q * scale)
+ * It needs a compressor: error_feedback = 1 with quant_bits = 0 is MLC_ERR_ARG.
  * A "fragment" for streaming synchronisation is simply a call with a subset of groups.
  */
 typedef struct {
@@ -149,8 +159,11 @@ typedef struct {
   int global_dtype;              /* mlc_dtype                                          */
   float* outer_momentum;         /* u, fp32, in/out                                    */
   uint8_t* const* codes;         /* HOST array of K device pointers, each
-                                    [count*m][n/2] packed codes; needed iff quant_bits */
+                                    [count*m][n*bits/8] packed codes; needed iff
+                                    quant_bits                                         */
   float* const* scales;          /* HOST array of K device pointers, each [count*m]    */
+  float* const* residuals;       /* HOST array of K device pointers E_k, fp32
+                                    [count][m][n], in/out; needed iff error_feedback   */
 } mlc_outer_group;
 
 typedef struct {
@@ -158,17 +171,21 @@ typedef struct {
   float eta_out;         /* outer learning rate                                        */
   float mu;              /* outer momentum                                             */
   int nesterov;          /* 1: eq. 3 as printed ; 0: theta_g <- theta_g - u            */
-  int quant_bits;        /* 0: exchange fp32 deltas ; 4: row-wise 4-bit codes          */
+  int quant_bits;        /* 0: exchange fp32 deltas ; 2, 4, 8: row-wise linear codes   */
   int write_back;        /* 1: copy the new theta_g into every worker replica          */
+  int error_feedback;    /* 1: compress beta E + Delta and keep what was not sent      */
+  float ef_beta;         /* decay of the residual (1 = keep all of it)                 */
 } mlc_outer_hparams;
 
-/* Needs no work space.  With quant_bits = 4 it first writes codes/scales (exactly what
- * muloco_quantize_delta writes) and then consumes them. */
+/* Needs no work space.  With quant_bits != 0 it first writes codes/scales (and with
+ * error feedback the residuals), exactly what muloco_quantize_delta writes, and then
+ * consumes them. */
 int muloco_outer_step(const mlc_outer_group* groups, int n_groups,
                       const mlc_outer_hparams* hp, void* stream);
 
-/* Only the compressor: fills codes[k] and scales[k] for every worker; nothing else is
- * written.  hp->quant_bits must be 4. */
+/* Only the compressor: fills codes[k] and scales[k] for every worker and, with error
+ * feedback, updates the residuals; nothing else is written.  hp->quant_bits must be 2, 4
+ * or 8. */
 int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups,
                           const mlc_outer_hparams* hp, void* stream);
 
@@ -186,8 +203,8 @@ enum {
   MLC_KERNEL_NORM = 2,        /* per-matrix 1 / (norm + eps)                           */
   MLC_KERNEL_UPDATE = 3,      /* parameter update                                      */
   MLC_KERNEL_OUTER = 4,       /* fused pseudogradient / average / outer update         */
-  MLC_KERNEL_QUANTIZE = 5,    /* row-wise 4-bit quantiser                              */
-  MLC_KERNEL_DEQUANT_OUTER = 6,/* dequantise + average + outer update                  */
+  MLC_KERNEL_QUANTIZE = 5,    /* row-wise quantiser (stand-alone compressor)           */
+  MLC_KERNEL_DEQUANT_OUTER = 6,/* (quantise +) dequantise + average + outer update     */
   MLC_KERNEL_CONVERT = 7,     /* layout / dtype conversion around newton_schulz        */
   MLC_KERNEL_FAMILIES = 8
 };

@@ -43,12 +43,14 @@ class _OuterGroup(C.Structure):
                 ("worker_params", C.POINTER(C.c_void_p)), ("worker_dtype", C.c_int),
                 ("global_param", C.c_void_p), ("global_dtype", C.c_int),
                 ("outer_momentum", C.c_void_p),
-                ("codes", C.POINTER(C.c_void_p)), ("scales", C.POINTER(C.c_void_p))]
+                ("codes", C.POINTER(C.c_void_p)), ("scales", C.POINTER(C.c_void_p)),
+                ("residuals", C.POINTER(C.c_void_p))]
 
 
 class _OuterHParams(C.Structure):
     _fields_ = [("K", C.c_int), ("eta_out", C.c_float), ("mu", C.c_float),
-                ("nesterov", C.c_int), ("quant_bits", C.c_int), ("write_back", C.c_int)]
+                ("nesterov", C.c_int), ("quant_bits", C.c_int), ("write_back", C.c_int),
+                ("error_feedback", C.c_int), ("ef_beta", C.c_float)]
 
 
 class _KernelTiming(C.Structure):
@@ -186,10 +188,13 @@ class OuterHParams:
     nesterov: bool = True
     quant_bits: int = 0
     write_back: bool = True
+    error_feedback: bool = False
+    ef_beta: float = 1.0
 
     def _c(self) -> _OuterHParams:
         return _OuterHParams(int(self.K), self.eta_out, self.mu, int(self.nesterov),
-                             int(self.quant_bits), int(self.write_back))
+                             int(self.quant_bits), int(self.write_back), int(self.error_feedback),
+                             self.ef_beta)
 
 
 @dataclass
@@ -198,8 +203,9 @@ class OuterGroup:
     worker_params: Sequence[torch.Tensor]
     global_param: torch.Tensor
     outer_momentum: Optional[torch.Tensor]
-    codes: Optional[Sequence[torch.Tensor]] = None     # K uint8 tensors [count*m, n/2]
+    codes: Optional[Sequence[torch.Tensor]] = None     # K uint8 tensors [count*m, n*bits/8]
     scales: Optional[Sequence[torch.Tensor]] = None    # K float32 tensors [count*m]
+    residuals: Optional[Sequence[torch.Tensor]] = None  # K float32 tensors like the parameters
     _keep: list = field(default_factory=list, repr=False)
 
     def _c(self) -> _OuterGroup:
@@ -221,19 +227,28 @@ class OuterGroup:
             if self.codes is None or self.scales is None or len(self.codes) != K or len(self.scales) != K:
                 raise ValueError("codes and scales must both hold K tensors")
             for c_, s_ in zip(self.codes, self.scales):
-                if c_.dtype != torch.uint8 or c_.numel() != cnt * m * (n // 2):
-                    raise ValueError("codes[k] must be uint8 with count*m*(n/2) elements")
+                if c_.dtype != torch.uint8 or c_.numel() not in [cnt * m * n * b // 8 for b in (2, 4, 8)]:
+                    raise ValueError("codes[k] must be uint8 with count*m*n*bits/8 elements")
                 if s_.dtype != torch.float32 or s_.numel() != cnt * m:
                     raise ValueError("scales[k] must be float32 with count*m elements")
             cp = (C.c_void_p * K)(*[_dev_ptr(c_, "codes[k]") for c_ in self.codes])
             sp = (C.c_void_p * K)(*[_dev_ptr(s_, "scales[k]") for s_ in self.scales])
-        self._keep = [wp, cp, sp]
+        rp = None
+        if self.residuals is not None:
+            if len(self.residuals) != K:
+                raise ValueError("residuals must hold K tensors")
+            for r_ in self.residuals:
+                if r_.dtype != torch.float32 or r_.numel() != cnt * m * n:
+                    raise ValueError("residuals[k] must be float32 with count*m*n elements")
+            rp = (C.c_void_p * K)(*[_dev_ptr(r_, "residuals[k]") for r_ in self.residuals])
+        self._keep = [wp, cp, sp, rp]
         return _OuterGroup(
             cnt, m, n, C.cast(wp, C.POINTER(C.c_void_p)), _dtype_code(self.worker_params[0]),
             _dev_ptr(self.global_param, "global_param"), _dtype_code(self.global_param),
             None if self.outer_momentum is None else _dev_ptr(self.outer_momentum, "outer_momentum"),
             None if cp is None else C.cast(cp, C.POINTER(C.c_void_p)),
-            None if sp is None else C.cast(sp, C.POINTER(C.c_void_p)))
+            None if sp is None else C.cast(sp, C.POINTER(C.c_void_p)),
+            None if rp is None else C.cast(rp, C.POINTER(C.c_void_p)))
 
 
 # ---------------------------------------------------------------------------------------
@@ -291,19 +306,25 @@ def _outer_array(groups: Sequence[OuterGroup]):
     return arr
 
 
-def muloco_outer_step(groups: Sequence[OuterGroup], hp: OuterHParams, stream=None) -> None:
+def _check_outer_groups(groups: Sequence[OuterGroup], hp: OuterHParams) -> None:
     for g in groups:
         if len(g.worker_params) != hp.K:
             raise ValueError("every group needs K worker tensors")
+        if hp.quant_bits in (2, 4, 8) and g.codes is not None:
+            want = g.global_param.numel() * hp.quant_bits // 8
+            if any(c_.numel() != want for c_ in g.codes):
+                raise ValueError("codes[k] must hold count*m*n*quant_bits/8 bytes")
+
+
+def muloco_outer_step(groups: Sequence[OuterGroup], hp: OuterHParams, stream=None) -> None:
+    _check_outer_groups(groups, hp)
     chp = hp._c()
     rc = library().muloco_outer_step(_outer_array(groups), len(groups), C.byref(chp), _stream(stream))
     _check(rc, "muloco_outer_step")
 
 
 def muloco_quantize_delta(groups: Sequence[OuterGroup], hp: OuterHParams, stream=None) -> None:
-    for g in groups:
-        if len(g.worker_params) != hp.K:
-            raise ValueError("every group needs K worker tensors")
+    _check_outer_groups(groups, hp)
     chp = hp._c()
     rc = library().muloco_quantize_delta(_outer_array(groups), len(groups), C.byref(chp),
                                          _stream(stream))

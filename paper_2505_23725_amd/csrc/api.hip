@@ -334,8 +334,10 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
   if (!hp || !groups) return MLC_ERR_NULL;
   if (n_groups < 0) return MLC_ERR_ARG;
   if (hp->K < 1 || hp->K > MLC_MAX_WORKERS) return MLC_ERR_ARG;
-  if (hp->quant_bits != 0 && hp->quant_bits != 4)
-    return (hp->quant_bits == 2 || hp->quant_bits == 8) ? MLC_ERR_UNSUPPORTED : MLC_ERR_ARG;
+  if (hp->quant_bits != 0 && hp->quant_bits != 2 && hp->quant_bits != 4 && hp->quant_bits != 8)
+    return MLC_ERR_ARG;
+  if (hp->error_feedback != 0 && hp->error_feedback != 1) return MLC_ERR_ARG;
+  if (hp->error_feedback && (hp->quant_bits == 0 || !(hp->ef_beta >= 0.f))) return MLC_ERR_ARG;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
     if (!g.worker_params || !g.global_param) return MLC_ERR_NULL;
@@ -350,23 +352,31 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
       if (!aligned16(g.worker_params[k])) return MLC_ERR_ARG;
     }
     if (hp->quant_bits) {
-      if (g.n % 2) return MLC_ERR_SHAPE;
+      if (g.n % (8 / hp->quant_bits)) return MLC_ERR_SHAPE;
       if (!g.codes || !g.scales) return MLC_ERR_NULL;
       for (int k = 0; k < hp->K; ++k) {
         if (!g.codes[k] || !g.scales[k]) return MLC_ERR_NULL;
         if (!aligned16(g.codes[k]) || !aligned16(g.scales[k])) return MLC_ERR_ARG;
       }
     }
+    if (hp->error_feedback) {
+      if (!g.residuals) return MLC_ERR_NULL;
+      for (int k = 0; k < hp->K; ++k) {
+        if (!g.residuals[k]) return MLC_ERR_NULL;
+        if (!aligned16(g.residuals[k])) return MLC_ERR_ARG;
+      }
+    }
   }
   return MLC_OK;
 }
 
-static void gather_ptrs(const mlc_outer_group& g, int K, bool quant, WorkerPtrs& w, CodePtrs& c,
-                        ScalePtrs& s) {
+static void gather_ptrs(const mlc_outer_group& g, int K, bool quant, bool ef, WorkerPtrs& w,
+                        CodePtrs& c, ScalePtrs& s, ResidualPtrs& e) {
   for (int k = 0; k < MLC_MAX_WORKERS; ++k) {
     w.p[k] = k < K ? g.worker_params[k] : nullptr;
     c.p[k] = (quant && k < K) ? g.codes[k] : nullptr;
     s.p[k] = (quant && k < K) ? g.scales[k] : nullptr;
+    e.p[k] = (ef && k < K) ? g.residuals[k] : nullptr;
   }
 }
 
@@ -374,14 +384,14 @@ int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups, const mlc
                           void* stream_) {
   int rc = check_outer(groups, n_groups, hp, false);
   if (rc != MLC_OK) return rc;
-  if (hp->quant_bits != 4) return MLC_ERR_ARG;
+  if (hp->quant_bits == 0) return MLC_ERR_ARG;
   hipStream_t stream = (hipStream_t)stream_;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
-    WorkerPtrs w; CodePtrs c; ScalePtrs s;
-    gather_ptrs(g, hp->K, true, w, c, s);
-    rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, g.count * g.m, g.n,
-                         hp->K, stream);
+    WorkerPtrs w; CodePtrs c; ScalePtrs s; ResidualPtrs e;
+    gather_ptrs(g, hp->K, true, hp->error_feedback != 0, w, c, s, e);
+    rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, e, g.count * g.m,
+                         g.n, hp->K, hp->quant_bits, hp->ef_beta, stream);
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;
@@ -394,23 +404,24 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
   hipStream_t stream = (hipStream_t)stream_;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
-    WorkerPtrs w; CodePtrs c; ScalePtrs s;
-    gather_ptrs(g, hp->K, hp->quant_bits != 0, w, c, s);
+    WorkerPtrs w; CodePtrs c; ScalePtrs s; ResidualPtrs e;
+    gather_ptrs(g, hp->K, hp->quant_bits != 0, hp->error_feedback != 0, w, c, s, e);
     if (hp->quant_bits) {
       // one pass when the row fits in registers, else quantise and then consume the codes
       rc = launch_quantize_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype,
-                                       g.outer_momentum, c, s, g.count * g.m, g.n, hp->K, hp->eta_out,
-                                       hp->mu, hp->nesterov, hp->write_back, stream);
+                                       g.outer_momentum, c, s, e, g.count * g.m, g.n, hp->K,
+                                       hp->quant_bits, hp->ef_beta, hp->eta_out, hp->mu, hp->nesterov,
+                                       hp->write_back, stream);
       if (rc != MLC_ERR_UNSUPPORTED) {
         if (rc != MLC_OK) return rc;
         continue;
       }
-      rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, g.count * g.m,
-                           g.n, hp->K, stream);
+      rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, e, g.count * g.m,
+                           g.n, hp->K, hp->quant_bits, hp->ef_beta, stream);
       if (rc != MLC_OK) return rc;
       rc = launch_dequant_outer(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
-                                c, s, g.count * g.m, g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
-                                hp->write_back, stream);
+                                c, s, g.count * g.m, g.n, hp->K, hp->quant_bits, hp->eta_out, hp->mu,
+                                hp->nesterov, hp->write_back, stream);
     } else {
       rc = launch_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
                               g.count * g.m * g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,

@@ -94,16 +94,19 @@ struct ScalePtrs { float* p[MLC_MAX_WORKERS]; };
 int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                        float* u, int64_t n_elems, int K, float eta_out, float mu, int nesterov,
                        int write_back, hipStream_t stream);
+// residual (error-feedback) accumulators per worker; all null = no error feedback
+struct ResidualPtrs { float* p[MLC_MAX_WORKERS]; };
 int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
-                    const CodePtrs& codes, const ScalePtrs& scales, int64_t rows, int64_t n,
-                    int K, hipStream_t stream);
+                    const CodePtrs& codes, const ScalePtrs& scales, const ResidualPtrs& ef,
+                    int64_t rows, int64_t n, int K, int bits, float ef_beta, hipStream_t stream);
 int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
-                                float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                                int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
+                                float* u, const CodePtrs& codes, const ScalePtrs& scales,
+                                const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
+                                float ef_beta, float eta_out, float mu, int nesterov, int write_back,
                                 hipStream_t stream);
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                          float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                         int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
-                         hipStream_t stream);
+                         int64_t n, int K, int bits, float eta_out, float mu, int nesterov,
+                         int write_back, hipStream_t stream);
 
 }  // namespace mlc

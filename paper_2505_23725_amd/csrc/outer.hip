@@ -1,7 +1,8 @@
 // HBM-bound kernels of the DiLoCo outer step (paper Sec. 4.1 eqs. 2-3, Algorithm 1 lines
 // after the inner loop, Algorithm 2 "compress parameter delta"):
 //   * fused pseudogradient / K-way average / outer Nesterov / write-back,
-//   * row-wise 4-bit linear quantiser of theta_g - theta_k (IEEE fp32, ties to even),
+//   * row-wise 2/4/8-bit linear quantiser of theta_g - theta_k (IEEE fp32, ties to even),
+//     optionally with error feedback (Algorithm 2, EF branch),
 //   * dequantise + K-way average + outer update + write-back.
 // The K worker replicas live on this GPU, so the average is a loop over K pointers
 // in a fixed order: ((d_1 + d_2) + ...) * (1/K).
@@ -96,70 +97,151 @@ __global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
   }
 }
 
-// ---- row-wise 4-bit quantiser: one wavefront per row, all K workers ------------------
-// Two passes over the row (absmax, then codes); the second pass re-reads data the first
-// pass just pulled through L2.
-__device__ __forceinline__ int quant_level(float delta, float scale) {
-  float q = rintf(delta / scale);           // IEEE division, round half to even
-  q = fminf(fmaxf(q, -7.f), 7.f);
+// ---- row-wise linear quantiser (Sec. 2 "Compressed Communication"; Algorithm 2) --------
+// bits = 2, 4 or 8: levels -qmax..qmax with qmax = 2^(bits-1) - 1, code = level + 2^(bits-1),
+// 8 / bits codes per byte with the lowest column in the lowest bits.  With error feedback
+// the value quantised is e = fl32(fl32(beta * E) + delta) and the residual becomes
+// E <- fl32(e - level * scale); both are fixed in fp32 (no fused multiply-add) so that codes
+// and residuals are reproducible bit for bit.
+__device__ __forceinline__ int quant_level(float v, float scale, float qmax) {
+  float q = rintf(v / scale);               // IEEE division, round half to even
+  q = fminf(fmaxf(q, -qmax), qmax);
   return (int)q;
 }
 
+__device__ __forceinline__ float ef_input(float delta, float residual, float beta) {
+  return __fadd_rn(__fmul_rn(beta, residual), delta);
+}
+
+// 8 adjacent levels of a row, first column c (a multiple of 8) <-> bits bytes of its codes
+__device__ __forceinline__ void store_codes8(uint8_t* crow, int c, const int (&q)[8], int bits) {
+  if (bits == 4) {
+    unsigned int p = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + 8) << (4 * j);
+    *reinterpret_cast<unsigned int*>(crow + c / 2) = p;
+  } else if (bits == 8) {
+    u32x2 p = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p.x |= (unsigned int)(q[j] + 128) << (8 * j);
+      p.y |= (unsigned int)(q[j + 4] + 128) << (8 * j);
+    }
+    *reinterpret_cast<u32x2*>(crow + c) = p;
+  } else {
+    unsigned int p = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + 2) << (2 * j);
+    *reinterpret_cast<unsigned short*>(crow + c / 4) = (unsigned short)p;
+  }
+}
+
+__device__ __forceinline__ void load_levels8(const uint8_t* crow, int c, int (&q)[8], int bits) {
+  if (bits == 4) {
+    const unsigned int p = *reinterpret_cast<const unsigned int*>(crow + c / 2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (4 * j)) & 0xfu) - 8;
+  } else if (bits == 8) {
+    const u32x2 p = *reinterpret_cast<const u32x2*>(crow + c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      q[j] = (int)((p.x >> (8 * j)) & 0xffu) - 128;
+      q[j + 4] = (int)((p.y >> (8 * j)) & 0xffu) - 128;
+    }
+  } else {
+    const unsigned int p = *reinterpret_cast<const unsigned short*>(crow + c / 4);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (2 * j)) & 0x3u) - 2;
+  }
+}
+
+// Two passes over the row (absmax, then codes), one wavefront per row, all K workers; the
+// second pass re-reads data the first pass just pulled through L2.  Rows whose length is
+// not a multiple of 8 go one code byte (8 / bits columns) per lane and step.
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
-    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, long rows, int n,
-    int K) {
+    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, ResidualPtrs ef,
+    long rows, int n, int K, int bits, float qmax, float ef_beta) {
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * (OT_THREADS / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const GT* tg = theta_g + row * n;
-  constexpr int W = VEC ? 8 : 2;            // elements per lane per step
+  const int W = VEC ? 8 : 8 / bits;         // elements per lane per step
+  const long row_bytes = (long)n * bits / 8;
   for (int k = 0; k < K; ++k) {
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + row * n;
+    float* res = ef.p[k] ? ef.p[k] + row * n : nullptr;
     float amax = 0.f;
     for (int c = lane * W; c < n; c += 64 * W) {
-      float a[8], b[8];
-      if (VEC) { Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b); }
-      else { a[0] = Ld<GT>::load1(tg + c); a[1] = Ld<GT>::load1(tg + c + 1);
-             b[0] = Ld<WT>::load1(tk + c); b[1] = Ld<WT>::load1(tk + c + 1); }
-#pragma unroll
-      for (int j = 0; j < W; ++j) amax = fmaxf(amax, fabsf(a[j] - b[j]));
+      float a[8], b[8], e[8];
+      if (VEC) {
+        Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
+        if (res) Ld<float>::load8(res + c, e);
+      } else {
+        for (int j = 0; j < W; ++j) {
+          a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
+          if (res) e[j] = res[c + j];
+        }
+      }
+      for (int j = 0; j < W; ++j) {
+        const float d = a[j] - b[j];
+        amax = fmaxf(amax, fabsf(res ? ef_input(d, e[j], ef_beta) : d));
+      }
     }
     amax = wave_max(amax);
-    const float scale = amax / 7.0f;
+    const float scale = amax / qmax;
     if (lane == 0) scales.p[k][row] = scale;
-    uint8_t* crow = codes.p[k] + row * (long)(n / 2);
+    uint8_t* crow = codes.p[k] + row * row_bytes;
     for (int c = lane * W; c < n; c += 64 * W) {
-      float a[8], b[8];
-      if (VEC) { Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b); }
-      else { a[0] = Ld<GT>::load1(tg + c); a[1] = Ld<GT>::load1(tg + c + 1);
-             b[0] = Ld<WT>::load1(tk + c); b[1] = Ld<WT>::load1(tk + c + 1); }
-      unsigned int packed = 0;
-#pragma unroll
-      for (int j = 0; j < W; ++j) {
-        const int q = (amax > 0.f) ? quant_level(a[j] - b[j], scale) : 0;
-        packed |= (unsigned int)(q + 8) << (4 * j);
+      float a[8], b[8], e[8];
+      if (VEC) {
+        Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
+        if (res) Ld<float>::load8(res + c, e);
+      } else {
+        for (int j = 0; j < W; ++j) {
+          a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
+          if (res) e[j] = res[c + j];
+        }
       }
-      if (VEC) *reinterpret_cast<unsigned int*>(crow + c / 2) = packed;
-      else crow[c / 2] = (uint8_t)packed;
+      int q[8];
+      for (int j = 0; j < W; ++j) {
+        const float d = a[j] - b[j];
+        const float v = res ? ef_input(d, e[j], ef_beta) : d;
+        q[j] = (amax > 0.f) ? quant_level(v, scale, qmax) : 0;
+        e[j] = __fsub_rn(v, __fmul_rn((float)q[j], scale));
+      }
+      if (VEC) {
+        store_codes8(crow, c, q, bits);
+        if (res) Ld<float>::store8(res + c, e);
+      } else {
+        unsigned int p = 0;
+        for (int j = 0; j < W; ++j) p |= (unsigned int)(q[j] + (1 << (bits - 1))) << (bits * j);
+        crow[c / W] = (uint8_t)p;
+        if (res)
+          for (int j = 0; j < W; ++j) res[c + j] = e[j];
+      }
     }
   }
 }
 
 // Single-pass variant: a group of G threads (a wavefront or the whole workgroup) owns a row
 // and keeps it in registers (NV vectors of 8 elements per thread), so theta_g is read once
-// for all K workers and every theta_k exactly once.  Same arithmetic as above.
-template <typename WT, typename GT, int NV, int G>
+// for all K workers and every theta_k exactly once.  Same arithmetic as above.  With
+// OUTER the dequantised values go straight into the mean and eq. 3 without re-reading
+// theta_g or the codes; codes and scales are written either way.
+template <typename WT, typename GT, int NV, int G, bool OUTER>
 __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
-    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, long rows, int n,
-    int K) {
+    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
+    ResidualPtrs ef, long rows, int n, int K, int bits, float qmax, float ef_beta, float eta,
+    float mu, float inv_k, int nesterov, int write_back) {
   constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
   __shared__ float red[2][OT_THREADS / 64];
   const int t = threadIdx.x % G;
   const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
   const bool live = row < rows;            // whole groups are live or not; no early return
   const long rbase = live ? row * n : 0;   // (the workgroup-wide barrier below needs everyone)
-  float tg[NV][8];
+  const long row_bytes = (long)n * bits / 8;
+  float tg[NV][8], acc[OUTER ? NV : 1][8];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (t + i * G) * 8;
@@ -167,9 +249,13 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
     else
 #pragma unroll
       for (int j = 0; j < 8; ++j) tg[i][j] = 0.f;
+    if constexpr (OUTER)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
   }
   for (int k = 0; k < K; ++k) {
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
+    float* res = ef.p[k] ? ef.p[k] + rbase : nullptr;
     float d[NV][8];
     float amax = 0.f;
 #pragma unroll
@@ -179,10 +265,15 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
         float b[8];
         Ld<WT>::load8(tk + c, b);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          d[i][j] = tg[i][j] - b[j];
-          amax = fmaxf(amax, fabsf(d[i][j]));
+        for (int j = 0; j < 8; ++j) d[i][j] = tg[i][j] - b[j];
+        if (res) {
+          float e[8];
+          Ld<float>::load8(res + c, e);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) d[i][j] = ef_input(d[i][j], e[j], ef_beta);
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(d[i][j]));
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) d[i][j] = 0.f;
@@ -194,105 +285,41 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
       __syncthreads();
       amax = fmaxf(fmaxf(red[k & 1][0], red[k & 1][1]), fmaxf(red[k & 1][2], red[k & 1][3]));
     }
-    const float scale = amax / 7.0f;
+    const float scale = amax / qmax;
     if (live && t == 0) scales.p[k][row] = scale;
-    uint8_t* crow = codes.p[k] + row * (long)(n / 2);
+    uint8_t* crow = codes.p[k] + row * row_bytes;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
       if (live && c < n) {
-        unsigned int packed = 0;
+        int q[8];
+        float e[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const int q = (amax > 0.f) ? quant_level(d[i][j], scale) : 0;
-          packed |= (unsigned int)(q + 8) << (4 * j);
+          q[j] = (amax > 0.f) ? quant_level(d[i][j], scale, qmax) : 0;
+          const float sent = __fmul_rn((float)q[j], scale);
+          e[j] = __fsub_rn(d[i][j], sent);
+          if constexpr (OUTER) acc[i][j] += sent;
         }
-        *reinterpret_cast<unsigned int*>(crow + c / 2) = packed;
+        store_codes8(crow, c, q, bits);
+        if (res) Ld<float>::store8(res + c, e);
       }
     }
   }
-}
-
-// Quantiser and outer update in one pass over a row held in registers: codes and scales are
-// written as the stand-alone quantiser writes them, and the dequantised deltas go straight
-// into the mean and eq. 3 without re-reading theta_g or the codes.
-template <typename WT, typename GT, int NV, int G>
-__global__ __launch_bounds__(OT_THREADS) void quantize_outer_rows_kernel(
-    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
-    long rows, int n, int K, float eta, float mu, float inv_k, int nesterov, int write_back) {
-  constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
-  __shared__ float red[2][OT_THREADS / 64];
-  const int t = threadIdx.x % G;
-  const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
-  const bool live = row < rows;
-  const long rbase = live ? row * n : 0;
-  float tg[NV][8], acc[NV][8];
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int c = (t + i * G) * 8;
-    if (live && c < n) Ld<GT>::load8(theta_g + rbase + c, tg[i]);
-    else
-#pragma unroll
-      for (int j = 0; j < 8; ++j) tg[i][j] = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
-  }
-  for (int k = 0; k < K; ++k) {
-    const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
-    float d[NV][8];
-    float amax = 0.f;
+  if constexpr (OUTER) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
       if (live && c < n) {
-        float b[8];
-        Ld<WT>::load8(tk + c, b);
+        float uv[8];
+        Ld<float>::load8(u + rbase + c, uv);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          d[i][j] = tg[i][j] - b[j];
-          amax = fmaxf(amax, fabsf(d[i][j]));
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) d[i][j] = 0.f;
+        for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j] * inv_k, eta, mu, nesterov);
+        Ld<GT>::store8(theta_g + rbase + c, tg[i]);
+        Ld<float>::store8(u + rbase + c, uv);
+        if (write_back)
+          for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + rbase + c, tg[i]);
       }
-    }
-    amax = wave_max(amax);
-    if constexpr (G > 64) {
-      if ((threadIdx.x & 63) == 0) red[k & 1][threadIdx.x >> 6] = amax;
-      __syncthreads();
-      amax = fmaxf(fmaxf(red[k & 1][0], red[k & 1][1]), fmaxf(red[k & 1][2], red[k & 1][3]));
-    }
-    const float scale = amax / 7.0f;
-    if (live && t == 0) scales.p[k][row] = scale;
-    uint8_t* crow = codes.p[k] + row * (long)(n / 2);
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = (t + i * G) * 8;
-      if (live && c < n) {
-        unsigned int packed = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int q = (amax > 0.f) ? quant_level(d[i][j], scale) : 0;
-          packed |= (unsigned int)(q + 8) << (4 * j);
-          acc[i][j] += __fmul_rn((float)q, scale);
-        }
-        *reinterpret_cast<unsigned int*>(crow + c / 2) = packed;
-      }
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int c = (t + i * G) * 8;
-    if (live && c < n) {
-      float uv[8];
-      Ld<float>::load8(u + rbase + c, uv);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j] * inv_k, eta, mu, nesterov);
-      Ld<GT>::store8(theta_g + rbase + c, tg[i]);
-      Ld<float>::store8(u + rbase + c, uv);
-      if (write_back)
-        for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + rbase + c, tg[i]);
     }
   }
 }
@@ -301,10 +328,11 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_outer_rows_kernel(
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
-    long rows, int n, int K, float eta, float mu, float inv_k, int nesterov, int write_back) {
-  constexpr int W = VEC ? 8 : 2;
+    long rows, int n, int K, int bits, float eta, float mu, float inv_k, int nesterov, int write_back) {
+  const int W = VEC ? 8 : 8 / bits;
   const int per_row = n / W;
   const long items = rows * per_row;
+  const long row_bytes = (long)n * bits / 8;
   for (long i = (long)blockIdx.x * OT_THREADS + threadIdx.x; i < items;
        i += (long)gridDim.x * OT_THREADS) {
     const long row = i / per_row;
@@ -312,21 +340,22 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     const long off = row * n + c;
     float tg[8], uv[8], acc[8];
     if (VEC) { Ld<GT>::load8(theta_g + off, tg); Ld<float>::load8(u + off, uv); }
-    else { tg[0] = Ld<GT>::load1(theta_g + off); tg[1] = Ld<GT>::load1(theta_g + off + 1);
-           uv[0] = u[off]; uv[1] = u[off + 1]; }
+    else
+      for (int j = 0; j < W; ++j) { tg[j] = Ld<GT>::load1(theta_g + off + j); uv[j] = u[off + j]; }
 #pragma unroll
-    for (int j = 0; j < W; ++j) acc[j] = 0.f;
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int k = 0; k < K; ++k) {
       const float sc = scales.p[k][row];
-      const uint8_t* cp = codes.p[k] + row * (long)(n / 2) + c / 2;
-      const unsigned int packed = VEC ? *reinterpret_cast<const unsigned int*>(cp) : (unsigned int)*cp;
-#pragma unroll
-      for (int j = 0; j < W; ++j) {
-        const int q = (int)((packed >> (4 * j)) & 0xfu) - 8;
-        acc[j] += __fmul_rn((float)q, sc);
+      const uint8_t* crow = codes.p[k] + row * row_bytes;
+      int q[8];
+      if (VEC) {
+        load_levels8(crow, c, q, bits);
+      } else {
+        const unsigned int p = crow[c / W];
+        for (int j = 0; j < W; ++j) q[j] = (int)((p >> (bits * j)) & ((1u << bits) - 1u)) - (1 << (bits - 1));
       }
+      for (int j = 0; j < W; ++j) acc[j] += __fmul_rn((float)q[j], sc);
     }
-#pragma unroll
     for (int j = 0; j < W; ++j) outer_update<GT>(tg[j], uv[j], acc[j] * inv_k, eta, mu, nesterov);
     if (VEC) {
       Ld<GT>::store8(theta_g + off, tg);
@@ -334,8 +363,7 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
       if (write_back)
         for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + off, tg);
     } else {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < W; ++j) {
         Ld<GT>::store1(theta_g + off + j, tg[j]);
         u[off + j] = uv[j];
         if (write_back)
@@ -382,15 +410,22 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
   return check_launch();
 }
 
+namespace {
+float quant_qmax(int bits) { return (float)((1 << (bits - 1)) - 1); }
+bool has_residuals(const ResidualPtrs& ef) { return ef.p[0] != nullptr; }
+}  // namespace
+
 int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
-                    const CodePtrs& codes, const ScalePtrs& scales, int64_t rows, int64_t n, int K,
-                    hipStream_t stream) {
+                    const CodePtrs& codes, const ScalePtrs& scales, const ResidualPtrs& ef,
+                    int64_t rows, int64_t n, int K, int bits, float ef_beta, hipStream_t stream) {
   const long blocks = (rows + OT_THREADS / 64 - 1) / (OT_THREADS / 64);
   if (blocks > 0x7fffffffL) return MLC_ERR_SHAPE;
-  const double bytes = (double)rows * n * (K * esize(worker_dtype) + esize(global_dtype) + 0.5 * K) +
+  const double bytes = (double)rows * n * (K * esize(worker_dtype) + esize(global_dtype) + bits / 8.0 * K +
+                                           (has_residuals(ef) ? 8.0 * K : 0.0)) +
                        (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_QUANTIZE, stream, 0.0, bytes);
   const bool vec = n % 8 == 0;
+  const float qmax = quant_qmax(bits);
   // single-pass register kernel: a wavefront per row up to 2048 columns, a workgroup per row
   // up to 24576; otherwise (or for odd row lengths) the two-pass kernel
   if (vec && n <= 24576 && !(worker_dtype == MLC_F32 && global_dtype == MLC_BF16)) {
@@ -400,9 +435,9 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
     const long rpb = OT_THREADS / g;
     const long nblk = (rows + rpb - 1) / rpb;
 #define MLC_QR(WT, GT, NV, G)                                                                     \
-  hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G>), dim3((unsigned)nblk),              \
-                     dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, (long)rows, \
-                     (int)n, K)
+  hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, false>), dim3((unsigned)nblk),       \
+                     dim3(OT_THREADS), 0, stream, w, (GT*)const_cast<void*>(theta_g), (float*)nullptr, \
+                     codes, scales, ef, (long)rows, (int)n, K, bits, qmax, ef_beta, 0.f, 0.f, 0.f, 0, 0)
 #define MLC_QR_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QR(WT, GT, 1, 64); else if (nv == 2) MLC_QR(WT, GT, 2, 64);   \
@@ -421,12 +456,12 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
   do {                                                                                            \
     if (vec)                                                                                      \
       hipLaunchKernelGGL((quantize_rows_kernel<WT, GT, true>), dim3((unsigned)blocks),            \
-                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales,       \
-                         (long)rows, (int)n, K);                                                  \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, ef,   \
+                         (long)rows, (int)n, K, bits, qmax, ef_beta);                             \
     else                                                                                          \
       hipLaunchKernelGGL((quantize_rows_kernel<WT, GT, false>), dim3((unsigned)blocks),           \
-                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales,       \
-                         (long)rows, (int)n, K);                                                  \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, ef,   \
+                         (long)rows, (int)n, K, bits, qmax, ef_beta);                             \
   } while (0)
   MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
 #undef MLC_CALL
@@ -435,12 +470,12 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
 
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                          float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                         int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
-                         hipStream_t stream) {
+                         int64_t n, int K, int bits, float eta_out, float mu, int nesterov,
+                         int write_back, hipStream_t stream) {
   const bool vec = n % 8 == 0;
-  const long items = rows * (n / (vec ? 8 : 2));
+  const long items = rows * (n / (vec ? 8 : 8 / bits));
   const int blocks = cap_blocks((items + OT_THREADS - 1) / OT_THREADS, 256 * 16);
-  const double bytes = (double)rows * n * (0.5 * K + 2 * esize(global_dtype) + 8 +
+  const double bytes = (double)rows * n * (bits / 8.0 * K + 2 * esize(global_dtype) + 8 +
                                            (write_back ? K * esize(worker_dtype) : 0)) +
                        (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
@@ -449,11 +484,11 @@ int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, i
   do {                                                                                            \
     if (vec)                                                                                      \
       hipLaunchKernelGGL((dequant_outer_kernel<WT, GT, true>), dim3(blocks), dim3(OT_THREADS), 0, \
-                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K,        \
+                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K, bits,  \
                          eta_out, mu, inv_k, nesterov, write_back);                               \
     else                                                                                          \
       hipLaunchKernelGGL((dequant_outer_kernel<WT, GT, false>), dim3(blocks), dim3(OT_THREADS), 0,\
-                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K,        \
+                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K, bits,  \
                          eta_out, mu, inv_k, nesterov, write_back);                               \
   } while (0)
   MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
@@ -464,8 +499,9 @@ int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, i
 // Returns MLC_ERR_UNSUPPORTED when the one-pass kernel does not cover the request (the
 // caller then runs the quantiser and the dequantising update as two launches).
 int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
-                                float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                                int64_t n, int K, float eta_out, float mu, int nesterov, int write_back,
+                                float* u, const CodePtrs& codes, const ScalePtrs& scales,
+                                const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
+                                float ef_beta, float eta_out, float mu, int nesterov, int write_back,
                                 hipStream_t stream) {
   if (n % 8 || n > 16384 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
     return MLC_ERR_UNSUPPORTED;
@@ -475,14 +511,16 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
   const long rpb = OT_THREADS / g;
   const long nblk = (rows + rpb - 1) / rpb;
   if (nblk > 0x7fffffffL) return MLC_ERR_SHAPE;
-  const double bytes = (double)rows * n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + 0.5 * K +
+  const double bytes = (double)rows * n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + bits / 8.0 * K +
+                                           (has_residuals(ef) ? 8.0 * K : 0.0) +
                                            2 * esize(global_dtype) + 8) + (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
   const float inv_k = 1.0f / (float)K;
+  const float qmax = quant_qmax(bits);
 #define MLC_QO(WT, GT, NV, G)                                                                     \
-  hipLaunchKernelGGL((quantize_outer_rows_kernel<WT, GT, NV, G>), dim3((unsigned)nblk),            \
-                     dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, (long)rows,   \
-                     (int)n, K, eta_out, mu, inv_k, nesterov, write_back)
+  hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, true>), dim3((unsigned)nblk),        \
+                     dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, ef, (long)rows, \
+                     (int)n, K, bits, qmax, ef_beta, eta_out, mu, inv_k, nesterov, write_back)
 #define MLC_QO_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QO(WT, GT, 1, 64); else if (nv == 2) MLC_QO(WT, GT, 2, 64);   \

@@ -19,7 +19,8 @@ from . import binding as B
 class MulocoJob:
     def __init__(self, workload: S.Workload, device="cuda:0", seed: int = 0,
                  layers: Optional[int] = None, K: Optional[int] = None,
-                 with_quant: bool = False, workspace_cap_bytes: Optional[int] = None,
+                 with_quant: bool = False, quant_bits: int = 4, with_ef: bool = False,
+                 workspace_cap_bytes: Optional[int] = None,
                  grad_dtype: Optional[torch.dtype] = None, generate_on: str = "cpu"):
         """generate_on: "cpu" draws every tensor with the CPU generator and copies it over
         (reproducible on the host for parity tests); "device" draws on the GPU (full-size
@@ -58,12 +59,16 @@ class MulocoJob:
                 self.workers[k].append(self.W[gi][k])
                 self.mom[k].append(self.M[gi][k])
                 self.grad[k].append(self.G[gi][k])
-        self.codes = self.scales = None
+        self.codes = self.scales = self.residuals = None
+        self.quant_bits = quant_bits
         if with_quant:
-            self.codes = [[torch.empty((c * m, n // 2), dtype=torch.uint8, device=self.device)
+            self.codes = [[torch.empty((c * m, n * quant_bits // 8), dtype=torch.uint8, device=self.device)
                            for (c, m, n) in self.shapes] for _ in range(self.K)]
             self.scales = [[torch.empty((c * m,), dtype=torch.float32, device=self.device)
                             for (c, m, n) in self.shapes] for _ in range(self.K)]
+        if with_ef:      # error-feedback residuals E_k, zero at the start (Algorithm 2)
+            self.residuals = [[torch.zeros(shp, dtype=torch.float32, device=self.device)
+                               for shp in self.shapes] for _ in range(self.K)]
         need = max(B.newton_schulz_workspace_bytes(self.K * s[0], s[1], s[2]) for s in self.shapes)
         floor = max(B.newton_schulz_workspace_min_bytes(s[1], s[2]) for s in self.shapes)
         if workspace_cap_bytes is not None:
@@ -141,20 +146,21 @@ class MulocoJob:
                                     self.M[gi].view(self.K * c, m, n), self.lr_scale(m, n)))
         return out
 
-    def outer_groups(self, quant: bool = False, group_ids=None) -> List[B.OuterGroup]:
+    def outer_groups(self, quant: bool = False, group_ids=None, ef: bool = False) -> List[B.OuterGroup]:
         ids = range(len(self.shapes)) if group_ids is None else group_ids
         out = []
         for gi in ids:
             ws = [self.workers[k][gi] for k in range(self.K)]
+            g = B.OuterGroup(ws, self.theta_g[gi], self.u[gi])
             if quant:
-                out.append(B.OuterGroup(ws, self.theta_g[gi], self.u[gi],
-                                        [self.codes[k][gi] for k in range(self.K)],
-                                        [self.scales[k][gi] for k in range(self.K)]))
-            else:
-                out.append(B.OuterGroup(ws, self.theta_g[gi], self.u[gi]))
+                g.codes = [self.codes[k][gi] for k in range(self.K)]
+                g.scales = [self.scales[k][gi] for k in range(self.K)]
+            if ef:
+                g.residuals = [self.residuals[k][gi] for k in range(self.K)]
+            out.append(g)
         return out
 
-    def layer_fragment(self, layer: int, quant: bool = False) -> List[B.OuterGroup]:
+    def layer_fragment(self, layer: int, quant: bool = False, ef: bool = False) -> List[B.OuterGroup]:
         """Outer-step groups covering one transformer layer (4 d x d, one d x f, one f x d):
         the unit a streaming schedule synchronises at a time."""
         out = []
@@ -162,22 +168,25 @@ class MulocoJob:
             per_layer = 4 if gi == 0 else 1
             sl = slice(layer * per_layer, (layer + 1) * per_layer)
             ws = [self.workers[k][gi][sl] for k in range(self.K)]
+            g = B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl])
             if quant:
                 rows = slice(layer * per_layer * m, (layer + 1) * per_layer * m)
-                out.append(B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl],
-                                        [self.codes[k][gi][rows] for k in range(self.K)],
-                                        [self.scales[k][gi][rows] for k in range(self.K)]))
-            else:
-                out.append(B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl]))
+                g.codes = [self.codes[k][gi][rows] for k in range(self.K)]
+                g.scales = [self.scales[k][gi][rows] for k in range(self.K)]
+            if ef:
+                g.residuals = [self.residuals[k][gi][sl] for k in range(self.K)]
+            out.append(g)
         return out
 
     def muon_hparams(self) -> B.MuonHParams:
         return B.MuonHParams(eta=self.wl.eta_in, weight_decay=self.wl.weight_decay, beta=self.wl.beta,
                              nesterov=True)
 
-    def outer_hparams(self, quant_bits: int = 0, write_back: bool = True) -> B.OuterHParams:
+    def outer_hparams(self, quant_bits: int = 0, write_back: bool = True, error_feedback: bool = False,
+                      ef_beta: float = 1.0) -> B.OuterHParams:
         return B.OuterHParams(K=self.K, eta_out=self.wl.eta_out, mu=self.wl.mu, nesterov=True,
-                              quant_bits=quant_bits, write_back=write_back)
+                              quant_bits=quant_bits, write_back=write_back,
+                              error_feedback=error_feedback, ef_beta=ef_beta)
 
     # -- the hot path -----------------------------------------------------------------------
     def inner_step(self) -> None:

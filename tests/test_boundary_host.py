@@ -132,11 +132,20 @@ def test_outer_step_argument_errors():
     assert call(group(), K=0) == -5
     assert call(group(), K=33) == -5
     assert call(group(), quant_bits=3) == -5
-    assert call(group(), quant_bits=8) == -7          # named by the paper, not built yet
+    assert call(group(), quant_bits=16) == -5
+    assert call(group(n=14), quant_bits=2) == -2      # four 2-bit codes per byte
     assert call(group(worker_dtype=9)) == -3
     assert call(group(m=0)) == -2
     assert call(group(n=15), quant_bits=4) == -2      # odd row length cannot be packed
     assert call(group(codes=None), quant_bits=4) == -1
+    # error feedback needs a compressor, residual accumulators and a decay that is not negative
+    assert call(group(), error_feedback=1, ef_beta=1.0) == -5
+    assert call(group(), error_feedback=2, quant_bits=4, ef_beta=1.0) == -5
+    assert call(group(), error_feedback=1, quant_bits=4, ef_beta=-0.5) == -5
+    assert call(group(), error_feedback=1, quant_bits=4, ef_beta=1.0) == -1     # residuals NULL
+    null_res = (C.c_void_p * K)(0x9000, None)
+    assert call(group(residuals=C.cast(null_res, C.POINTER(C.c_void_p))), error_feedback=1, quant_bits=4,
+                ef_beta=1.0) == -1
     assert call(group(), fn="muloco_quantize_delta", quant_bits=0) == -5
     null_worker = (C.c_void_p * K)(0x1000, None)
     assert call(group(worker_params=C.cast(null_worker, C.POINTER(C.c_void_p)))) == -1
