@@ -25,6 +25,12 @@ with Nesterov momentum) and Algorithm 2's "compress parameter delta" branch.  Re
       (q, scale) = quantise(e) row-wise as above;  communicated value = float(q) * scale
       E_k  <- fl32(e - float(q) * scale)
   and the communicated values are averaged in place of the deltas.
+* Second quantisation (Sec. 2 "Collectives": one dequantise-reduce-quantise between the
+  all-to-all reduce-scatter and the all-gather): the reduced value is quantised again before
+  it is used.  The stage is fixed in fp32 like the first one,
+      acc   = ((s_1 + s_2) + ...) + s_K   with s_k = float(q_k) * scale_k, summed in fp32
+      psi   = fl32(acc * fl32(1 / K))
+      (q', scale') = quantise(psi) row-wise;  the outer update uses float(q') * scale'.
 """
 import numpy as np
 
@@ -142,8 +148,23 @@ def dequantize_rowwise(q, scale):
     return (np.asarray(q, np.float32) * np.asarray(scale, np.float32)[:, None]).astype(np.float32)
 
 
+def requantize_mean(sent_f32, bits=4):
+    """The dequantise-reduce-quantise step between the two collectives: fp32 mean of the
+    workers' dequantised values in worker order, quantised row-wise again.
+
+    Returns (q', scale', psi float32 before the second quantisation)."""
+    K = len(sent_f32)
+    acc = np.asarray(sent_f32[0], dtype=np.float32).copy()
+    for s in sent_f32[1:]:
+        acc = (acc + np.asarray(s, dtype=np.float32)).astype(np.float32)
+    inv_k = np.float32(1.0) / np.float32(K)
+    psi = (acc * inv_k).astype(np.float32)
+    q, scale = quantize_values_rowwise(psi, bits)
+    return q, scale, psi
+
+
 def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0,
-               residuals=None, ef_beta=1.0):
+               residuals=None, ef_beta=1.0, second_quantisation=False):
     """One outer step on one 2-D tensor [rows, n].
 
     theta_g, thetas[k]: stored values (float64 holding fp32/bf16-representable numbers).
@@ -172,7 +193,13 @@ def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bit
         assert residuals is None, "error feedback needs a compressor"
         for th in thetas:
             deltas.append(pseudogradient(theta_g, th))
-    psi = average(deltas)
+    if second_quantisation:
+        assert quant_bits, "the second quantisation needs a compressor"
+        q2, s2, _ = requantize_mean([d.astype(np.float32) for d in deltas], quant_bits)
+        out["mean_q"], out["mean_scales"] = q2, s2
+        psi = dequantize_rowwise(q2, s2).astype(np.float64)
+    else:
+        psi = average(deltas)
     theta, u = outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov)
     out.update(theta=theta, u=u, psi=psi)
     return out

@@ -174,3 +174,52 @@ def test_brute_force_nearest_level_2_and_8_bit():
                     assert mid < Fraction(1, 2 ** 16), (bits, i, j)
                     mism += 1
         assert mism <= 2
+
+
+# ---- second quantisation (dequantise - reduce - quantise between the two collectives) ----
+
+def test_second_quantisation_of_one_worker_changes_nothing():
+    """K = 1: the mean is the dequantised delta itself, and quantising dequantised values
+    again reproduces them, so the second stage must be the identity."""
+    r = _rng(21)
+    tg = _f32(r.standard_normal((10, 32)) * 0.02).astype(np.float64)
+    th = (_f32(tg) - _f32(r.standard_normal((10, 32)) * 1e-2)).astype(np.float64)
+    u0 = r.standard_normal((10, 32)) * 1e-3
+    for bits in (2, 4, 8):
+        one = diloco.outer_step(tg, u0, [th], eta_out=0.7, mu=0.9, quant_bits=bits)
+        two = diloco.outer_step(tg, u0, [th], eta_out=0.7, mu=0.9, quant_bits=bits, second_quantisation=True)
+        assert np.array_equal(two["mean_q"], one["q"][0])
+        assert np.all(np.abs(two["mean_scales"] - one["scales"][0]) <= np.spacing(one["scales"][0]))
+        assert np.max(np.abs(two["theta"] - one["theta"])) <= 1e-9 * np.max(np.abs(one["theta"]))
+
+
+def test_second_quantisation_hand_rows():
+    # sent values [7, 1, -3, 0] and [7, 3, -4, 1] (scales 1): fp32 mean [7, 2, -3.5, 0.5];
+    # amax 7 -> scale 1; -3.5 ties to -4, 0.5 ties to 0
+    q, s, psi = diloco.requantize_mean([_f32([[7, 1, -3, 0]]), _f32([[7, 3, -4, 1]])], 4)
+    assert psi[0].tolist() == [7, 2, -3.5, 0.5] and s[0] == np.float32(1)
+    assert q[0].tolist() == [7, 2, -4, 0]
+    # three workers: the mean is acc * fl32(1/3), not acc / 3
+    a = _f32([[3, 6, -9, 21]])
+    q, s, psi = diloco.requantize_mean([a, a, a], 4)
+    third = np.float32(1) / np.float32(3)
+    assert np.array_equal(psi, ((a + a).astype(np.float32) + a).astype(np.float32) * third)
+
+
+def test_second_quantisation_error_bound_and_use_in_the_update():
+    r = _rng(22)
+    tg = _f32(r.standard_normal((8, 48)) * 0.02).astype(np.float64)
+    ths = [(_f32(tg) - _f32(r.standard_normal((8, 48)) * 1e-2)).astype(np.float64) for _ in range(4)]
+    u0 = r.standard_normal((8, 48)) * 1e-3
+    one = diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8, quant_bits=4)
+    two = diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8, quant_bits=4, second_quantisation=True)
+    # first-stage codes are untouched; psi moves by at most half a second-stage step
+    for k in range(4):
+        assert np.array_equal(one["q"][k], two["q"][k])
+    half = two["mean_scales"][:, None].astype(np.float64) / 2
+    assert np.all(np.abs(two["psi"] - one["psi"]) <= half * (1 + 1e-6) + 1e-9)
+    assert np.max(np.abs(two["psi"] - one["psi"])) > 0
+    psi = diloco.dequantize_rowwise(two["mean_q"], two["mean_scales"]).astype(np.float64)
+    u = 0.8 * u0 + 0.9 * psi
+    assert np.max(np.abs(two["u"] - u)) < 1e-18
+    assert np.max(np.abs(two["theta"] - (tg - 0.8 * u - 0.9 * psi))) < 1e-17
