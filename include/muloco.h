@@ -148,6 +148,14 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     the row of e is quantised as above and its dequantised values are what is averaged
  *     E_k <- fl32(e - (float)q * scale)
  * It needs a compressor: error_feedback = 1 with quant_bits = 0 is MLC_ERR_ARG.
+ *
+ * Second quantisation (paper Sec. 2 "Collectives": one dequantise-reduce-quantise between
+ * the all-to-all reduce-scatter and the all-gather), with second_quantisation = 1: the mean
+ *     Psi = fl32(((s_1 + s_2) + ... + s_K) * fl32(1 / K)),  s_k the dequantised values, fp32
+ * is quantised row-wise again with the same bit width, and eq. 3 uses its dequantised
+ * value.  Its codes and scales are written to mean_codes / mean_scales when these are not
+ * NULL.  Rows longer than 16384 or not a multiple of 8 are MLC_ERR_UNSUPPORTED, and so is
+ * the pair of fp32 workers with a bf16 global copy.
  * A "fragment" for streaming synchronisation is simply a call with a subset of groups.
  */
 typedef struct {
@@ -164,6 +172,9 @@ typedef struct {
   float* const* scales;          /* HOST array of K device pointers, each [count*m]    */
   float* const* residuals;       /* HOST array of K device pointers E_k, fp32
                                     [count][m][n], in/out; needed iff error_feedback   */
+  uint8_t* mean_codes;           /* device, [count*m][n*bits/8], or NULL: codes of the
+                                    second quantisation                                */
+  float* mean_scales;            /* device, [count*m], or NULL                         */
 } mlc_outer_group;
 
 typedef struct {
@@ -175,6 +186,7 @@ typedef struct {
   int write_back;        /* 1: copy the new theta_g into every worker replica          */
   int error_feedback;    /* 1: compress beta E + Delta and keep what was not sent      */
   float ef_beta;         /* decay of the residual (1 = keep all of it)                 */
+  int second_quantisation; /* 1: quantise the mean again before the outer update       */
 } mlc_outer_hparams;
 
 /* Needs no work space.  With quant_bits != 0 it first writes codes/scales (and with

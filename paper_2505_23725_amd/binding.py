@@ -44,13 +44,15 @@ class _OuterGroup(C.Structure):
                 ("global_param", C.c_void_p), ("global_dtype", C.c_int),
                 ("outer_momentum", C.c_void_p),
                 ("codes", C.POINTER(C.c_void_p)), ("scales", C.POINTER(C.c_void_p)),
-                ("residuals", C.POINTER(C.c_void_p))]
+                ("residuals", C.POINTER(C.c_void_p)),
+                ("mean_codes", C.c_void_p), ("mean_scales", C.c_void_p)]
 
 
 class _OuterHParams(C.Structure):
     _fields_ = [("K", C.c_int), ("eta_out", C.c_float), ("mu", C.c_float),
                 ("nesterov", C.c_int), ("quant_bits", C.c_int), ("write_back", C.c_int),
-                ("error_feedback", C.c_int), ("ef_beta", C.c_float)]
+                ("error_feedback", C.c_int), ("ef_beta", C.c_float),
+                ("second_quantisation", C.c_int)]
 
 
 class _KernelTiming(C.Structure):
@@ -190,11 +192,12 @@ class OuterHParams:
     write_back: bool = True
     error_feedback: bool = False
     ef_beta: float = 1.0
+    second_quantisation: bool = False
 
     def _c(self) -> _OuterHParams:
         return _OuterHParams(int(self.K), self.eta_out, self.mu, int(self.nesterov),
                              int(self.quant_bits), int(self.write_back), int(self.error_feedback),
-                             self.ef_beta)
+                             self.ef_beta, int(self.second_quantisation))
 
 
 @dataclass
@@ -206,6 +209,8 @@ class OuterGroup:
     codes: Optional[Sequence[torch.Tensor]] = None     # K uint8 tensors [count*m, n*bits/8]
     scales: Optional[Sequence[torch.Tensor]] = None    # K float32 tensors [count*m]
     residuals: Optional[Sequence[torch.Tensor]] = None  # K float32 tensors like the parameters
+    mean_codes: Optional[torch.Tensor] = None           # uint8 [count*m, n*bits/8]: second quantisation
+    mean_scales: Optional[torch.Tensor] = None          # float32 [count*m]
     _keep: list = field(default_factory=list, repr=False)
 
     def _c(self) -> _OuterGroup:
@@ -241,6 +246,11 @@ class OuterGroup:
                 if r_.dtype != torch.float32 or r_.numel() != cnt * m * n:
                     raise ValueError("residuals[k] must be float32 with count*m*n elements")
             rp = (C.c_void_p * K)(*[_dev_ptr(r_, "residuals[k]") for r_ in self.residuals])
+        if self.mean_codes is not None and self.mean_codes.dtype != torch.uint8:
+            raise TypeError("mean_codes must be uint8")
+        if self.mean_scales is not None and (self.mean_scales.dtype != torch.float32
+                                             or self.mean_scales.numel() != cnt * m):
+            raise ValueError("mean_scales must be float32 with count*m elements")
         self._keep = [wp, cp, sp, rp]
         return _OuterGroup(
             cnt, m, n, C.cast(wp, C.POINTER(C.c_void_p)), _dtype_code(self.worker_params[0]),
@@ -248,7 +258,9 @@ class OuterGroup:
             None if self.outer_momentum is None else _dev_ptr(self.outer_momentum, "outer_momentum"),
             None if cp is None else C.cast(cp, C.POINTER(C.c_void_p)),
             None if sp is None else C.cast(sp, C.POINTER(C.c_void_p)),
-            None if rp is None else C.cast(rp, C.POINTER(C.c_void_p)))
+            None if rp is None else C.cast(rp, C.POINTER(C.c_void_p)),
+            None if self.mean_codes is None else _dev_ptr(self.mean_codes, "mean_codes"),
+            None if self.mean_scales is None else _dev_ptr(self.mean_scales, "mean_scales"))
 
 
 # ---------------------------------------------------------------------------------------
@@ -314,6 +326,8 @@ def _check_outer_groups(groups: Sequence[OuterGroup], hp: OuterHParams) -> None:
             want = g.global_param.numel() * hp.quant_bits // 8
             if any(c_.numel() != want for c_ in g.codes):
                 raise ValueError("codes[k] must hold count*m*n*quant_bits/8 bytes")
+            if g.mean_codes is not None and g.mean_codes.numel() != want:
+                raise ValueError("mean_codes must hold count*m*n*quant_bits/8 bytes")
 
 
 def muloco_outer_step(groups: Sequence[OuterGroup], hp: OuterHParams, stream=None) -> None:

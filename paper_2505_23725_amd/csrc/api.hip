@@ -338,6 +338,8 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
     return MLC_ERR_ARG;
   if (hp->error_feedback != 0 && hp->error_feedback != 1) return MLC_ERR_ARG;
   if (hp->error_feedback && (hp->quant_bits == 0 || !(hp->ef_beta >= 0.f))) return MLC_ERR_ARG;
+  if (hp->second_quantisation != 0 && hp->second_quantisation != 1) return MLC_ERR_ARG;
+  if (hp->second_quantisation && hp->quant_bits == 0) return MLC_ERR_ARG;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
     if (!g.worker_params || !g.global_param) return MLC_ERR_NULL;
@@ -358,6 +360,12 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
         if (!g.codes[k] || !g.scales[k]) return MLC_ERR_NULL;
         if (!aligned16(g.codes[k]) || !aligned16(g.scales[k])) return MLC_ERR_ARG;
       }
+    }
+    if (hp->second_quantisation) {
+      if ((g.mean_codes && !aligned16(g.mean_codes)) || (g.mean_scales && !aligned16(g.mean_scales)))
+        return MLC_ERR_ARG;
+      if (g.n % 8 || g.n > 16384 || (g.worker_dtype == MLC_F32 && g.global_dtype == MLC_BF16))
+        return MLC_ERR_UNSUPPORTED;
     }
     if (hp->error_feedback) {
       if (!g.residuals) return MLC_ERR_NULL;
@@ -411,8 +419,10 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
       rc = launch_quantize_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype,
                                        g.outer_momentum, c, s, e, g.count * g.m, g.n, hp->K,
                                        hp->quant_bits, hp->ef_beta, hp->eta_out, hp->mu, hp->nesterov,
-                                       hp->write_back, stream);
-      if (rc != MLC_ERR_UNSUPPORTED) {
+                                       hp->write_back, hp->second_quantisation,
+                                       hp->second_quantisation ? g.mean_codes : nullptr,
+                                       hp->second_quantisation ? g.mean_scales : nullptr, stream);
+      if (rc != MLC_ERR_UNSUPPORTED || hp->second_quantisation) {
         if (rc != MLC_OK) return rc;
         continue;
       }

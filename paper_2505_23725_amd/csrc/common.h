@@ -103,6 +103,7 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
                                 float* u, const CodePtrs& codes, const ScalePtrs& scales,
                                 const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
                                 float ef_beta, float eta_out, float mu, int nesterov, int write_back,
+                                int requant, uint8_t* mean_codes, float* mean_scales,
                                 hipStream_t stream);
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                          float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,

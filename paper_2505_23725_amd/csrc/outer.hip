@@ -233,9 +233,11 @@ template <typename WT, typename GT, int NV, int G, bool OUTER>
 __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
     WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
     ResidualPtrs ef, long rows, int n, int K, int bits, float qmax, float ef_beta, float eta,
-    float mu, float inv_k, int nesterov, int write_back) {
+    float mu, float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes,
+    float* mean_scales) {
   constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
   __shared__ float red[2][OT_THREADS / 64];
+  __shared__ float red2[OT_THREADS / 64];
   const int t = threadIdx.x % G;
   const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
   const bool live = row < rows;            // whole groups are live or not; no early return
@@ -308,13 +310,47 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
   }
   if constexpr (OUTER) {
 #pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __fmul_rn(acc[i][j], inv_k);     // Psi
+    if (requant) {
+      // Second quantisation (the dequantise-reduce-quantise step between the two modelled
+      // collectives): Psi is quantised row-wise again and its dequantised value is used.
+      float amax = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(acc[i][j]));    // dead lanes hold 0
+      amax = wave_max(amax);
+      if constexpr (G > 64) {
+        if ((threadIdx.x & 63) == 0) red2[threadIdx.x >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(red2[0], red2[1]), fmaxf(red2[2], red2[3]));
+      }
+      const float scale = amax / qmax;
+      if (mean_scales && live && t == 0) mean_scales[row] = scale;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = (t + i * G) * 8;
+        if (live && c < n) {
+          int q[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            q[j] = (amax > 0.f) ? quant_level(acc[i][j], scale, qmax) : 0;
+            acc[i][j] = __fmul_rn((float)q[j], scale);
+          }
+          if (mean_codes) store_codes8(mean_codes + row * row_bytes, c, q, bits);
+        }
+      }
+    }
+#pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
       if (live && c < n) {
         float uv[8];
         Ld<float>::load8(u + rbase + c, uv);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j] * inv_k, eta, mu, nesterov);
+        for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j], eta, mu, nesterov);
         Ld<GT>::store8(theta_g + rbase + c, tg[i]);
         Ld<float>::store8(u + rbase + c, uv);
         if (write_back)
@@ -437,7 +473,8 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
 #define MLC_QR(WT, GT, NV, G)                                                                     \
   hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, false>), dim3((unsigned)nblk),       \
                      dim3(OT_THREADS), 0, stream, w, (GT*)const_cast<void*>(theta_g), (float*)nullptr, \
-                     codes, scales, ef, (long)rows, (int)n, K, bits, qmax, ef_beta, 0.f, 0.f, 0.f, 0, 0)
+                     codes, scales, ef, (long)rows, (int)n, K, bits, qmax, ef_beta, 0.f, 0.f, 0.f, 0, 0, 0, \
+                     (uint8_t*)nullptr, (float*)nullptr)
 #define MLC_QR_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QR(WT, GT, 1, 64); else if (nv == 2) MLC_QR(WT, GT, 2, 64);   \
@@ -502,6 +539,7 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
                                 float* u, const CodePtrs& codes, const ScalePtrs& scales,
                                 const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
                                 float ef_beta, float eta_out, float mu, int nesterov, int write_back,
+                                int requant, uint8_t* mean_codes, float* mean_scales,
                                 hipStream_t stream) {
   if (n % 8 || n > 16384 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
     return MLC_ERR_UNSUPPORTED;
@@ -513,6 +551,7 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
   if (nblk > 0x7fffffffL) return MLC_ERR_SHAPE;
   const double bytes = (double)rows * n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + bits / 8.0 * K +
                                            (has_residuals(ef) ? 8.0 * K : 0.0) +
+                                           (mean_codes ? bits / 8.0 : 0.0) +
                                            2 * esize(global_dtype) + 8) + (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
   const float inv_k = 1.0f / (float)K;
@@ -520,7 +559,8 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
 #define MLC_QO(WT, GT, NV, G)                                                                     \
   hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, true>), dim3((unsigned)nblk),        \
                      dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, ef, (long)rows, \
-                     (int)n, K, bits, qmax, ef_beta, eta_out, mu, inv_k, nesterov, write_back)
+                     (int)n, K, bits, qmax, ef_beta, eta_out, mu, inv_k, nesterov, write_back, requant, \
+                     mean_codes, mean_scales)
 #define MLC_QO_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QO(WT, GT, 1, 64); else if (nv == 2) MLC_QO(WT, GT, 2, 64);   \

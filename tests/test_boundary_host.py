@@ -143,6 +143,11 @@ def test_outer_step_argument_errors():
     assert call(group(), error_feedback=2, quant_bits=4, ef_beta=1.0) == -5
     assert call(group(), error_feedback=1, quant_bits=4, ef_beta=-0.5) == -5
     assert call(group(), error_feedback=1, quant_bits=4, ef_beta=1.0) == -1     # residuals NULL
+    # the second quantisation needs a compressor and rows the one-pass kernel can hold
+    assert call(group(), second_quantisation=1) == -5
+    assert call(group(), second_quantisation=2, quant_bits=4) == -5
+    assert call(group(n=20480), second_quantisation=1, quant_bits=4) == -7
+    assert call(group(n=12), second_quantisation=1, quant_bits=4) == -7
     null_res = (C.c_void_p * K)(0x9000, None)
     assert call(group(residuals=C.cast(null_res, C.POINTER(C.c_void_p))), error_feedback=1, quant_bits=4,
                 ef_beta=1.0) == -1

@@ -145,3 +145,56 @@ def test_error_feedback_off_leaves_residuals_alone():
                             [to_f64(w).reshape(-1, n) for w in ws0], eta_out=0.9, mu=0.8, quant_bits=4)
     for k in range(K):
         assert np.array_equal(codes[k].cpu().numpy(), diloco.pack_codes4(ref["q"][k]))
+
+
+SQ_CASES = [
+    # cnt, m, n, K, worker dtype, global dtype, bits, error feedback
+    (2, 64, 128, 3, torch.bfloat16, torch.float32, 4, False),
+    (1, 50, 1000, 4, torch.bfloat16, torch.float32, 4, True),
+    (1, 12, 5120, 2, torch.bfloat16, torch.bfloat16, 4, False),
+    (1, 6, 16384, 2, torch.bfloat16, torch.float32, 8, False),        # longest supported row
+    (1, 24, 768, 8, torch.bfloat16, torch.float32, 2, True),
+    (1, 9, 2048, 1, torch.float32, torch.float32, 4, False),          # K = 1: second stage is the identity
+]
+
+
+@pytest.mark.parametrize("cnt,m,n,K,wd,gd,bits,ef", SQ_CASES)
+def test_second_quantisation_bit_exact(cnt, m, n, K, wd, gd, bits, ef):
+    seed = 11 * n + K + bits
+    tg0, ws0, u0 = _inputs(cnt, m, n, K, wd, gd, seed)
+    tg, u = tg0.to(DEV), u0.to(DEV)
+    ws = [w.to(DEV) for w in ws0]
+    codes, scales = _alloc(cnt, m, n, K, bits)
+    res0 = [S.normal((cnt, m, n), 1e-3, seed, 40 + k) for k in range(K)] if ef else None
+    res = [r.to(DEV) for r in res0] if ef else None
+    mcodes = torch.full((cnt * m, n * bits // 8), 0xAA, dtype=torch.uint8, device=DEV)
+    mscales = torch.full((cnt * m,), -1.0, dtype=torch.float32, device=DEV)
+    grp = mlc.OuterGroup(ws, tg, u, codes, scales, res, mcodes, mscales)
+    hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, quant_bits=bits, error_feedback=ef, ef_beta=0.9,
+                          second_quantisation=True)
+    mlc.muloco_outer_step([grp], hp)
+    torch.cuda.synchronize()
+    ref = diloco.outer_step(to_f64(tg0).reshape(-1, n), to_f64(u0).reshape(-1, n),
+                            [to_f64(w).reshape(-1, n) for w in ws0], eta_out=0.9, mu=0.8, quant_bits=bits,
+                            residuals=[r.numpy().reshape(-1, n) for r in res0] if ef else None, ef_beta=0.9,
+                            second_quantisation=True)
+    for k in range(K):
+        assert np.array_equal(codes[k].cpu().numpy(), diloco.pack_codes(ref["q"][k], bits)), f"worker {k} codes"
+        assert _same_bits(scales[k].cpu().numpy(), ref["scales"][k])
+        if ef:
+            assert _same_bits(res[k].cpu().numpy().reshape(-1, n), ref["residuals"][k])
+    want = diloco.pack_codes(ref["mean_q"], bits)
+    got = mcodes.cpu().numpy()
+    assert np.array_equal(got, want), f"{(got != want).sum()} bytes of the second-stage codes differ"
+    assert _same_bits(mscales.cpu().numpy(), ref["mean_scales"]), "second-stage scales differ"
+    assert_fp32_close(u.cpu().reshape(-1, n), ref["u"], "outer momentum")
+    assert_stored_close(tg.cpu().reshape(-1, n), ref["theta"], "global parameters")
+    if K == 1 and not ef:
+        assert np.array_equal(got, codes[0].cpu().numpy())
+    # without buffers for the second-stage codes the update is the same
+    tg2, u2 = tg0.to(DEV), u0.to(DEV)
+    c2, s2 = _alloc(cnt, m, n, K, bits)
+    res2 = [r.to(DEV) for r in res0] if ef else None
+    mlc.muloco_outer_step([mlc.OuterGroup([w.to(DEV) for w in ws0], tg2, u2, c2, s2, res2)], hp)
+    torch.cuda.synchronize()
+    assert torch.equal(tg2, tg) and torch.equal(u2, u)
