@@ -31,6 +31,14 @@ with Nesterov momentum) and Algorithm 2's "compress parameter delta" branch.  Re
       acc   = ((s_1 + s_2) + ...) + s_K   with s_k = float(q_k) * scale_k, summed in fp32
       psi   = fl32(acc * fl32(1 / K))
       (q', scale') = quantise(psi) row-wise;  the outer update uses float(q') * scale'.
+* Offset form (the paper's wording: uniformly spaced levels over a fixed range, an offset and
+  a number of levels): the range is [lo, hi] = [min, max] of the values instead of
+  [-amax, amax], with L = 2^bits - 1 steps,
+      scale = fl32(fl32(hi - lo) / L)
+      q_j   = clamp(rint(fl32(fl32(v_j - lo) / scale)), 0, L), ties to even; 0 if scale == 0
+      code  = q_j (unsigned);  dequantised value = fl32(fl32(float(q_j) * scale) + lo).
+* Scope: "row" takes the range over each row, "matrix" over each whole matrix (the paper's
+  global variant, one range per parameter tensor); scale and lo are then stored per matrix.
 """
 import numpy as np
 
@@ -74,6 +82,59 @@ def quantize_values_rowwise(values_f32, bits=4):
     q = np.clip(np.rint(ratio), -qmax, qmax)
     q = np.where(scale[:, None] > 0, q, 0.0).astype(np.int8)
     return q, scale
+
+
+def _range_groups(v, scope, rows_per_matrix):
+    """[groups, rows in group, n] view of a 2-D array for the chosen scope."""
+    rows, n = v.shape
+    if scope == "row":
+        return v.reshape(rows, 1, n)
+    assert scope == "matrix" and rows_per_matrix and rows % rows_per_matrix == 0
+    return v.reshape(rows // rows_per_matrix, rows_per_matrix, n)
+
+
+def quantize_values(values_f32, bits=4, offset=False, scope="row", rows_per_matrix=None):
+    """Linear quantisation of a 2-D float32 array in any of the forms described above.
+
+    Returns (q int16 [rows, n], scale float32 [groups], lo float32 [groups]); lo is zero for
+    the symmetric form.  groups = rows for scope "row", rows / rows_per_matrix for "matrix"."""
+    v = np.asarray(values_f32, dtype=np.float32)
+    assert v.ndim == 2
+    g = _range_groups(v, scope, rows_per_matrix)
+    if not offset:
+        qmax = np.float32(2 ** (bits - 1) - 1)
+        amax = np.max(np.abs(g), axis=(1, 2)).astype(np.float32)
+        scale = (amax / qmax).astype(np.float32)
+        lo = np.zeros_like(scale)
+        safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+        ratio = (g / safe[:, None, None]).astype(np.float32)
+        q = np.clip(np.rint(ratio), -qmax, qmax)
+    else:
+        levels = np.float32(2 ** bits - 1)
+        lo = np.min(g, axis=(1, 2)).astype(np.float32)
+        hi = np.max(g, axis=(1, 2)).astype(np.float32)
+        scale = ((hi - lo).astype(np.float32) / levels).astype(np.float32)
+        safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+        shifted = (g - lo[:, None, None]).astype(np.float32)
+        ratio = (shifted / safe[:, None, None]).astype(np.float32)
+        q = np.clip(np.rint(ratio), 0, levels)
+    q = np.where(scale[:, None, None] > 0, q, 0.0).astype(np.int16).reshape(v.shape)
+    return q, scale, lo
+
+
+def dequantize_values(q, scale, lo, offset=False, scope="row", rows_per_matrix=None):
+    """Inverse of quantize_values, in fp32: float(q) * scale, plus lo in the offset form."""
+    q = np.asarray(q)
+    g = _range_groups(q.astype(np.float32), scope, rows_per_matrix)
+    out = (g * np.asarray(scale, np.float32)[:, None, None]).astype(np.float32)
+    if offset:
+        out = (out + np.asarray(lo, np.float32)[:, None, None]).astype(np.float32)
+    return out.reshape(q.shape)
+
+
+def pack_codes_unsigned(q, bits):
+    """Offset-form levels 0 .. 2^bits - 1 are stored as they are, packed like pack_codes."""
+    return pack_codes(np.asarray(q, np.int16) - 2 ** (bits - 1), bits)
 
 
 def quantize_rowwise(theta_g_f32, theta_k_f32, bits=4):
@@ -164,40 +225,53 @@ def requantize_mean(sent_f32, bits=4):
 
 
 def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0,
-               residuals=None, ef_beta=1.0, second_quantisation=False):
+               residuals=None, ef_beta=1.0, second_quantisation=False, quant_offset=False,
+               quant_scope="row", rows_per_matrix=None):
     """One outer step on one 2-D tensor [rows, n].
 
     theta_g, thetas[k]: stored values (float64 holding fp32/bf16-representable numbers).
     residuals: per-worker EF accumulators E_k (float32) or None for no error feedback.
     Returns dict with theta (new global), u, psi, for the quantised path the per-worker
-    levels q[k] and scales[k], and with error feedback the new residuals."""
+    levels q[k], scales[k] and (offset form) offsets[k], and with error feedback the new
+    residuals."""
     theta_g = np.asarray(theta_g, np.float64)
+    form = dict(offset=quant_offset, scope=quant_scope, rows_per_matrix=rows_per_matrix)
     out = {}
     deltas = []
     if quant_bits:
-        out["q"], out["scales"] = [], []
+        out["q"], out["scales"], out["offsets"] = [], [], []
         if residuals is not None:
             out["residuals"] = []
+        tg32 = theta_g.astype(np.float32)
         for k, th in enumerate(thetas):
-            tg32 = theta_g.astype(np.float32)
             tk32 = np.asarray(th, np.float64).astype(np.float32)
+            v = (tg32 - tk32).astype(np.float32)
+            if residuals is not None:      # Algorithm 2, EF branch
+                E = np.asarray(residuals[k], dtype=np.float32)
+                v = ((np.float32(ef_beta) * E).astype(np.float32) + v).astype(np.float32)
+            q, s, lo = quantize_values(v, quant_bits, **form)
+            sent = dequantize_values(q, s, lo, **form)
             if residuals is not None:
-                q, s, e_new = error_feedback_compress(tg32, tk32, residuals[k], ef_beta, quant_bits)
-                out["residuals"].append(e_new)
-            else:
-                q, s = quantize_rowwise(tg32, tk32, quant_bits)
-            out["q"].append(q)
+                out["residuals"].append((v - sent).astype(np.float32))
+            out["q"].append(q.astype(np.int8) if not quant_offset else q)
             out["scales"].append(s)
-            deltas.append(dequantize_rowwise(q, s).astype(np.float64))
+            out["offsets"].append(lo)
+            deltas.append(sent.astype(np.float64))
     else:
         assert residuals is None, "error feedback needs a compressor"
         for th in thetas:
             deltas.append(pseudogradient(theta_g, th))
     if second_quantisation:
         assert quant_bits, "the second quantisation needs a compressor"
-        q2, s2, _ = requantize_mean([d.astype(np.float32) for d in deltas], quant_bits)
-        out["mean_q"], out["mean_scales"] = q2, s2
-        psi = dequantize_rowwise(q2, s2).astype(np.float64)
+        K = len(deltas)
+        acc = deltas[0].astype(np.float32)
+        for d in deltas[1:]:
+            acc = (acc + d.astype(np.float32)).astype(np.float32)
+        psi32 = (acc * (np.float32(1.0) / np.float32(K))).astype(np.float32)
+        q2, s2, lo2 = quantize_values(psi32, quant_bits, **form)
+        out["mean_q"], out["mean_scales"], out["mean_offsets"] = (
+            q2.astype(np.int8) if not quant_offset else q2), s2, lo2
+        psi = dequantize_values(q2, s2, lo2, **form).astype(np.float64)
     else:
         psi = average(deltas)
     theta, u = outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov)

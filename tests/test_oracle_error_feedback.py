@@ -36,13 +36,13 @@ def test_first_round_is_the_plain_quantiser_and_the_residual_is_its_error():
 
 
 def test_hand_rows_with_decay():
-    # round 1: e = 0.5 * [2,-4,0.5,0] + [6,-5,0.25,0] = [7,-7,0.5,0]; scale 1; 0.5 ties to 0
+    # first synchronisation: e = 0.5 * [2,-4,0.5,0] + [6,-5,0.25,0] = [7,-7,0.5,0]; scale 1; 0.5 ties to 0
     tk = _f32([[0, 0, 0, 0]])
     E = _f32([[2, -4, 0.5, 0]])
     q, s, E1 = diloco.error_feedback_compress(_f32([[6, -5, 0.25, 0]]), tk, E, 0.5, 4)
     assert s[0] == np.float32(1) and q[0].tolist() == [7, -7, 0, 0]
     assert E1[0].tolist() == [0, 0, 0.5, 0]
-    # round 2: e = 0.5 * [0,0,0.5,0] + [7,0,1.25,0] = [7,0,1.5,0]; 1.5 ties to 2: more is
+    # second synchronisation: e = 0.5 * [0,0,0.5,0] + [7,0,1.25,0] = [7,0,1.5,0]; 1.5 ties to 2: more is
     # sent than was there, so the residual is negative
     q, s, E2 = diloco.error_feedback_compress(_f32([[7, 0, 1.25, 0]]), tk, E1, 0.5, 4)
     assert q[0].tolist() == [7, 0, 2, 0] and E2[0].tolist() == [0, 0, -0.5, 0]
