@@ -143,11 +143,15 @@ def main() -> int:
     quant_alone["frac_hbm"] = quant_alone["GBps"] / PEAK_HBM_GBS
 
     # Also outside the timed region: the quantised outer step over the whole model with error
-    # feedback (4 bit) and in its 8- and 2-bit forms, when their extra buffers fit in memory.
+    # feedback (4 bit), in its 8- and 2-bit forms, in the offset form and with one range per
+    # matrix (one more pass over the deltas), when their extra buffers fit in memory.
     variants = {}
     free_bytes = torch.cuda.mem_get_info()[0]
     n_elems = sum(c * m * n for (c, m, n) in job.shapes)
-    for name, bits, ef in (("4bit_error_feedback", 4, True), ("8bit", 8, False), ("2bit", 2, False)):
+    for name, bits, ef, offset, per_matrix in (("4bit_error_feedback", 4, True, False, False),
+                                               ("8bit", 8, False, False, False), ("2bit", 2, False, False, False),
+                                               ("4bit_offset_form", 4, False, True, False),
+                                               ("4bit_range_per_matrix", 4, False, False, True)):
         need = job.K * n_elems * (bits / 8 + (4 if ef else 0)) + (1 << 30)
         if need > free_bytes:
             variants[name] = None
@@ -156,11 +160,15 @@ def main() -> int:
         for gi, (c, m, n) in enumerate(job.shapes):
             g = mlc.OuterGroup([job.workers[k][gi] for k in range(job.K)], job.theta_g[gi], job.u[gi])
             g.codes = [torch.empty((c * m, n * bits // 8), dtype=torch.uint8, device="cuda:0") for _ in range(job.K)]
-            g.scales = [job.scales[k][gi] for k in range(job.K)]
+            ranges = c if per_matrix else c * m
+            g.scales = [torch.empty((ranges,), dtype=torch.float32, device="cuda:0") for _ in range(job.K)]
+            if offset:
+                g.offsets = [torch.empty((ranges,), dtype=torch.float32, device="cuda:0") for _ in range(job.K)]
             if ef:
                 g.residuals = [torch.zeros((c, m, n), dtype=torch.float32, device="cuda:0") for _ in range(job.K)]
             groups.append(g)
         hpv = job.outer_hparams(quant_bits=bits, error_feedback=ef, ef_beta=0.9)
+        hpv.quant_offset, hpv.quant_per_matrix = offset, per_matrix
         mlc.muloco_outer_step(groups, hpv)              # warm-up
         torch.cuda.synchronize()
         mlc.muloco_timing_enable(True)

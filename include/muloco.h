@@ -142,6 +142,14 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     dequantised value = (float)q * scale
  * n must be a multiple of 8 / bits.
  *
+ * Offset form (quant_offset = 1; the paper's wording: levels over a fixed range, an offset
+ * and a number of levels): the range is [lo, hi] = [min, max] of the values, L = 2^bits - 1,
+ *     scale = fl32(hi - lo) / L;  q = clamp(rint(fl32(delta - lo) / scale), 0, L), 0 if scale = 0
+ *     code = q;  dequantised value = fl32(fl32((float)q * scale) + lo);  lo goes to offsets.
+ * Scope (quant_per_matrix = 1; the paper's global variant): one range per matrix instead of
+ * one per row; scales[k] and offsets[k] then hold count entries, and the call makes one more
+ * pass over the deltas to find the ranges.
+ *
  * Error feedback (paper Sec. 2 "Compressed Communication"; Algorithm 2, EF branch), with
  * error_feedback = 1 and one fp32 residual E_k per worker, also fixed in fp32:
  *     e   = fl32(fl32(ef_beta * E_k) + delta)      (product, then sum; not fused)
@@ -154,8 +162,8 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     Psi = fl32(((s_1 + s_2) + ... + s_K) * fl32(1 / K)),  s_k the dequantised values, fp32
  * is quantised row-wise again with the same bit width, and eq. 3 uses its dequantised
  * value.  Its codes and scales are written to mean_codes / mean_scales when these are not
- * NULL.  Rows longer than 16384 or not a multiple of 8 are MLC_ERR_UNSUPPORTED, and so is
- * the pair of fp32 workers with a bf16 global copy.
+ * NULL.  Rows longer than 16384 or not a multiple of 8 are MLC_ERR_UNSUPPORTED, and so are
+ * the pair of fp32 workers with a bf16 global copy and the per-matrix scope.
  * A "fragment" for streaming synchronisation is simply a call with a subset of groups.
  */
 typedef struct {
@@ -169,12 +177,17 @@ typedef struct {
   uint8_t* const* codes;         /* HOST array of K device pointers, each
                                     [count*m][n*bits/8] packed codes; needed iff
                                     quant_bits                                         */
-  float* const* scales;          /* HOST array of K device pointers, each [count*m]    */
+  float* const* scales;          /* HOST array of K device pointers, each [count*m]
+                                    ([count] with quant_per_matrix)                    */
   float* const* residuals;       /* HOST array of K device pointers E_k, fp32
                                     [count][m][n], in/out; needed iff error_feedback   */
   uint8_t* mean_codes;           /* device, [count*m][n*bits/8], or NULL: codes of the
                                     second quantisation                                */
   float* mean_scales;            /* device, [count*m], or NULL                         */
+  float* const* offsets;         /* HOST array of K device pointers like scales: lower
+                                    ends of the ranges; needed iff quant_offset        */
+  float* mean_offsets;           /* device, [count*m], or NULL (second quantisation in
+                                    the offset form)                                   */
 } mlc_outer_group;
 
 typedef struct {
@@ -187,6 +200,8 @@ typedef struct {
   int error_feedback;    /* 1: compress beta E + Delta and keep what was not sent      */
   float ef_beta;         /* decay of the residual (1 = keep all of it)                 */
   int second_quantisation; /* 1: quantise the mean again before the outer update       */
+  int quant_offset;      /* 1: range [min, max] with an offset instead of [-amax, amax] */
+  int quant_per_matrix;  /* 1: one range per matrix instead of one per row             */
 } mlc_outer_hparams;
 
 /* Needs no work space.  With quant_bits != 0 it first writes codes/scales (and with

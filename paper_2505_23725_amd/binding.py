@@ -45,14 +45,16 @@ class _OuterGroup(C.Structure):
                 ("outer_momentum", C.c_void_p),
                 ("codes", C.POINTER(C.c_void_p)), ("scales", C.POINTER(C.c_void_p)),
                 ("residuals", C.POINTER(C.c_void_p)),
-                ("mean_codes", C.c_void_p), ("mean_scales", C.c_void_p)]
+                ("mean_codes", C.c_void_p), ("mean_scales", C.c_void_p),
+                ("offsets", C.POINTER(C.c_void_p)), ("mean_offsets", C.c_void_p)]
 
 
 class _OuterHParams(C.Structure):
     _fields_ = [("K", C.c_int), ("eta_out", C.c_float), ("mu", C.c_float),
                 ("nesterov", C.c_int), ("quant_bits", C.c_int), ("write_back", C.c_int),
                 ("error_feedback", C.c_int), ("ef_beta", C.c_float),
-                ("second_quantisation", C.c_int)]
+                ("second_quantisation", C.c_int), ("quant_offset", C.c_int),
+                ("quant_per_matrix", C.c_int)]
 
 
 class _KernelTiming(C.Structure):
@@ -193,11 +195,14 @@ class OuterHParams:
     error_feedback: bool = False
     ef_beta: float = 1.0
     second_quantisation: bool = False
+    quant_offset: bool = False
+    quant_per_matrix: bool = False
 
     def _c(self) -> _OuterHParams:
         return _OuterHParams(int(self.K), self.eta_out, self.mu, int(self.nesterov),
                              int(self.quant_bits), int(self.write_back), int(self.error_feedback),
-                             self.ef_beta, int(self.second_quantisation))
+                             self.ef_beta, int(self.second_quantisation), int(self.quant_offset),
+                             int(self.quant_per_matrix))
 
 
 @dataclass
@@ -211,6 +216,8 @@ class OuterGroup:
     residuals: Optional[Sequence[torch.Tensor]] = None  # K float32 tensors like the parameters
     mean_codes: Optional[torch.Tensor] = None           # uint8 [count*m, n*bits/8]: second quantisation
     mean_scales: Optional[torch.Tensor] = None          # float32 [count*m]
+    offsets: Optional[Sequence[torch.Tensor]] = None    # K float32 tensors like scales (offset form)
+    mean_offsets: Optional[torch.Tensor] = None         # float32 [count*m]
     _keep: list = field(default_factory=list, repr=False)
 
     def _c(self) -> _OuterGroup:
@@ -234,8 +241,8 @@ class OuterGroup:
             for c_, s_ in zip(self.codes, self.scales):
                 if c_.dtype != torch.uint8 or c_.numel() not in [cnt * m * n * b // 8 for b in (2, 4, 8)]:
                     raise ValueError("codes[k] must be uint8 with count*m*n*bits/8 elements")
-                if s_.dtype != torch.float32 or s_.numel() != cnt * m:
-                    raise ValueError("scales[k] must be float32 with count*m elements")
+                if s_.dtype != torch.float32 or s_.numel() not in (cnt * m, cnt):
+                    raise ValueError("scales[k] must be float32 with count*m (or count) elements")
             cp = (C.c_void_p * K)(*[_dev_ptr(c_, "codes[k]") for c_ in self.codes])
             sp = (C.c_void_p * K)(*[_dev_ptr(s_, "scales[k]") for s_ in self.scales])
         rp = None
@@ -251,7 +258,18 @@ class OuterGroup:
         if self.mean_scales is not None and (self.mean_scales.dtype != torch.float32
                                              or self.mean_scales.numel() != cnt * m):
             raise ValueError("mean_scales must be float32 with count*m elements")
-        self._keep = [wp, cp, sp, rp]
+        op = None
+        if self.offsets is not None:
+            if len(self.offsets) != K:
+                raise ValueError("offsets must hold K tensors")
+            for o_ in self.offsets:
+                if o_.dtype != torch.float32 or o_.numel() not in (cnt * m, cnt):
+                    raise ValueError("offsets[k] must be float32 with count*m (or count) elements")
+            op = (C.c_void_p * K)(*[_dev_ptr(o_, "offsets[k]") for o_ in self.offsets])
+        if self.mean_offsets is not None and (self.mean_offsets.dtype != torch.float32
+                                              or self.mean_offsets.numel() != cnt * m):
+            raise ValueError("mean_offsets must be float32 with count*m elements")
+        self._keep = [wp, cp, sp, rp, op]
         return _OuterGroup(
             cnt, m, n, C.cast(wp, C.POINTER(C.c_void_p)), _dtype_code(self.worker_params[0]),
             _dev_ptr(self.global_param, "global_param"), _dtype_code(self.global_param),
@@ -260,7 +278,9 @@ class OuterGroup:
             None if sp is None else C.cast(sp, C.POINTER(C.c_void_p)),
             None if rp is None else C.cast(rp, C.POINTER(C.c_void_p)),
             None if self.mean_codes is None else _dev_ptr(self.mean_codes, "mean_codes"),
-            None if self.mean_scales is None else _dev_ptr(self.mean_scales, "mean_scales"))
+            None if self.mean_scales is None else _dev_ptr(self.mean_scales, "mean_scales"),
+            None if op is None else C.cast(op, C.POINTER(C.c_void_p)),
+            None if self.mean_offsets is None else _dev_ptr(self.mean_offsets, "mean_offsets"))
 
 
 # ---------------------------------------------------------------------------------------
@@ -328,6 +348,11 @@ def _check_outer_groups(groups: Sequence[OuterGroup], hp: OuterHParams) -> None:
                 raise ValueError("codes[k] must hold count*m*n*quant_bits/8 bytes")
             if g.mean_codes is not None and g.mean_codes.numel() != want:
                 raise ValueError("mean_codes must hold count*m*n*quant_bits/8 bytes")
+            cnt_, m_, _ = _shape3(g.global_param)
+            ranges = cnt_ if hp.quant_per_matrix else cnt_ * m_
+            for t_ in list(g.scales or []) + list(g.offsets or []):
+                if t_.numel() != ranges:
+                    raise ValueError("scales[k] / offsets[k] must hold one entry per range")
 
 
 def muloco_outer_step(groups: Sequence[OuterGroup], hp: OuterHParams, stream=None) -> None:

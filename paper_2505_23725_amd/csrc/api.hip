@@ -340,6 +340,11 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
   if (hp->error_feedback && (hp->quant_bits == 0 || !(hp->ef_beta >= 0.f))) return MLC_ERR_ARG;
   if (hp->second_quantisation != 0 && hp->second_quantisation != 1) return MLC_ERR_ARG;
   if (hp->second_quantisation && hp->quant_bits == 0) return MLC_ERR_ARG;
+  if ((hp->quant_offset != 0 && hp->quant_offset != 1) ||
+      (hp->quant_per_matrix != 0 && hp->quant_per_matrix != 1))
+    return MLC_ERR_ARG;
+  if ((hp->quant_offset || hp->quant_per_matrix) && hp->quant_bits == 0) return MLC_ERR_ARG;
+  if (hp->second_quantisation && hp->quant_per_matrix) return MLC_ERR_UNSUPPORTED;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
     if (!g.worker_params || !g.global_param) return MLC_ERR_NULL;
@@ -361,8 +366,17 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
         if (!aligned16(g.codes[k]) || !aligned16(g.scales[k])) return MLC_ERR_ARG;
       }
     }
+    if (hp->quant_offset) {
+      if (!g.offsets) return MLC_ERR_NULL;
+      for (int k = 0; k < hp->K; ++k) {
+        if (!g.offsets[k]) return MLC_ERR_NULL;
+        if (!aligned16(g.offsets[k])) return MLC_ERR_ARG;
+      }
+    }
+    if (hp->quant_per_matrix && g.count > 65535) return MLC_ERR_SHAPE;
     if (hp->second_quantisation) {
-      if ((g.mean_codes && !aligned16(g.mean_codes)) || (g.mean_scales && !aligned16(g.mean_scales)))
+      if ((g.mean_codes && !aligned16(g.mean_codes)) || (g.mean_scales && !aligned16(g.mean_scales)) ||
+          (g.mean_offsets && !aligned16(g.mean_offsets)))
         return MLC_ERR_ARG;
       if (g.n % 8 || g.n > 16384 || (g.worker_dtype == MLC_F32 && g.global_dtype == MLC_BF16))
         return MLC_ERR_UNSUPPORTED;
@@ -378,14 +392,22 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
   return MLC_OK;
 }
 
-static void gather_ptrs(const mlc_outer_group& g, int K, bool quant, bool ef, WorkerPtrs& w,
-                        CodePtrs& c, ScalePtrs& s, ResidualPtrs& e) {
+struct OuterPtrs { WorkerPtrs w; CodePtrs c; ScalePtrs s; OffsetPtrs o; ResidualPtrs e; };
+
+static void gather_ptrs(const mlc_outer_group& g, const mlc_outer_hparams& hp, OuterPtrs& p) {
+  const int K = hp.K;
+  const bool quant = hp.quant_bits != 0;
   for (int k = 0; k < MLC_MAX_WORKERS; ++k) {
-    w.p[k] = k < K ? g.worker_params[k] : nullptr;
-    c.p[k] = (quant && k < K) ? g.codes[k] : nullptr;
-    s.p[k] = (quant && k < K) ? g.scales[k] : nullptr;
-    e.p[k] = (ef && k < K) ? g.residuals[k] : nullptr;
+    p.w.p[k] = k < K ? g.worker_params[k] : nullptr;
+    p.c.p[k] = (quant && k < K) ? g.codes[k] : nullptr;
+    p.s.p[k] = (quant && k < K) ? g.scales[k] : nullptr;
+    p.o.p[k] = (hp.quant_offset && k < K) ? g.offsets[k] : nullptr;
+    p.e.p[k] = (hp.error_feedback && k < K) ? g.residuals[k] : nullptr;
   }
+}
+
+static QuantForm form_of(const mlc_outer_group& g, const mlc_outer_hparams& hp) {
+  return make_quant_form(hp.quant_bits, hp.quant_offset, hp.quant_per_matrix ? g.m : 0, hp.ef_beta);
 }
 
 int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
@@ -396,10 +418,16 @@ int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups, const mlc
   hipStream_t stream = (hipStream_t)stream_;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
-    WorkerPtrs w; CodePtrs c; ScalePtrs s; ResidualPtrs e;
-    gather_ptrs(g, hp->K, true, hp->error_feedback != 0, w, c, s, e);
-    rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, e, g.count * g.m,
-                         g.n, hp->K, hp->quant_bits, hp->ef_beta, stream);
+    OuterPtrs p;
+    gather_ptrs(g, *hp, p);
+    const QuantForm form = form_of(g, *hp);
+    if (hp->quant_per_matrix) {
+      rc = launch_matrix_ranges(p.w, g.worker_dtype, g.global_param, g.global_dtype, p.s, p.o, p.e, g.count,
+                                g.m, g.n, hp->K, form, stream);
+      if (rc != MLC_OK) return rc;
+    }
+    rc = launch_quantize(p.w, g.worker_dtype, g.global_param, g.global_dtype, p.c, p.s, p.o, p.e,
+                         g.count * g.m, g.n, hp->K, form, stream);
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;
@@ -412,28 +440,35 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
   hipStream_t stream = (hipStream_t)stream_;
   for (int i = 0; i < n_groups; ++i) {
     const mlc_outer_group& g = groups[i];
-    WorkerPtrs w; CodePtrs c; ScalePtrs s; ResidualPtrs e;
-    gather_ptrs(g, hp->K, hp->quant_bits != 0, hp->error_feedback != 0, w, c, s, e);
+    OuterPtrs p;
+    gather_ptrs(g, *hp, p);
     if (hp->quant_bits) {
+      const QuantForm form = form_of(g, *hp);
+      if (hp->quant_per_matrix) {
+        rc = launch_matrix_ranges(p.w, g.worker_dtype, g.global_param, g.global_dtype, p.s, p.o, p.e,
+                                  g.count, g.m, g.n, hp->K, form, stream);
+        if (rc != MLC_OK) return rc;
+      }
       // one pass when the row fits in registers, else quantise and then consume the codes
-      rc = launch_quantize_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype,
-                                       g.outer_momentum, c, s, e, g.count * g.m, g.n, hp->K,
-                                       hp->quant_bits, hp->ef_beta, hp->eta_out, hp->mu, hp->nesterov,
-                                       hp->write_back, hp->second_quantisation,
+      rc = launch_quantize_outer_fused(p.w, g.worker_dtype, g.global_param, g.global_dtype,
+                                       g.outer_momentum, p.c, p.s, p.o, p.e, g.count * g.m, g.n, hp->K,
+                                       form, hp->eta_out, hp->mu, hp->nesterov, hp->write_back,
+                                       hp->second_quantisation,
                                        hp->second_quantisation ? g.mean_codes : nullptr,
-                                       hp->second_quantisation ? g.mean_scales : nullptr, stream);
+                                       hp->second_quantisation ? g.mean_scales : nullptr,
+                                       hp->second_quantisation ? g.mean_offsets : nullptr, stream);
       if (rc != MLC_ERR_UNSUPPORTED || hp->second_quantisation) {
         if (rc != MLC_OK) return rc;
         continue;
       }
-      rc = launch_quantize(w, g.worker_dtype, g.global_param, g.global_dtype, c, s, e, g.count * g.m,
-                           g.n, hp->K, hp->quant_bits, hp->ef_beta, stream);
+      rc = launch_quantize(p.w, g.worker_dtype, g.global_param, g.global_dtype, p.c, p.s, p.o, p.e,
+                           g.count * g.m, g.n, hp->K, form, stream);
       if (rc != MLC_OK) return rc;
-      rc = launch_dequant_outer(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
-                                c, s, g.count * g.m, g.n, hp->K, hp->quant_bits, hp->eta_out, hp->mu,
+      rc = launch_dequant_outer(p.w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
+                                p.c, p.s, p.o, g.count * g.m, g.n, hp->K, form, hp->eta_out, hp->mu,
                                 hp->nesterov, hp->write_back, stream);
     } else {
-      rc = launch_outer_fused(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
+      rc = launch_outer_fused(p.w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum,
                               g.count * g.m * g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
                               hp->write_back, stream);
     }

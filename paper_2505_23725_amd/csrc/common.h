@@ -41,6 +41,11 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
   return v;
 }
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off, 64));
+  return v;
+}
 
 static inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
 
@@ -96,18 +101,38 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
                        int write_back, hipStream_t stream);
 // residual (error-feedback) accumulators per worker; all null = no error feedback
 struct ResidualPtrs { float* p[MLC_MAX_WORKERS]; };
+// Form of the linear quantiser (see muloco.h).
+struct QuantForm {
+  int bits;              // 2, 4 or 8
+  int offset;            // 0: range [-amax, amax]; 1: range [min, max], stored with an offset
+  int rows_per_range;    // 0: one range per row; m: one range per matrix of m rows
+  float levels;          // 2^(bits-1) - 1 without offset, 2^bits - 1 with
+  int code_bias;         // stored code = level + code_bias: 2^(bits-1) without offset, 0 with
+  float ef_beta;         // decay of the error-feedback residual
+};
+QuantForm make_quant_form(int bits, int offset, int64_t rows_per_range, float ef_beta);
+// per-worker lower ends of the ranges (offset form); all null otherwise
+typedef ScalePtrs OffsetPtrs;
+// Ranges per matrix, written to scales (and offsets) ahead of the quantiser proper.
+int launch_matrix_ranges(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
+                         const ScalePtrs& scales, const OffsetPtrs& offsets, const ResidualPtrs& ef,
+                         int64_t count, int64_t m, int64_t n, int K, const QuantForm& form,
+                         hipStream_t stream);
 int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
-                    const CodePtrs& codes, const ScalePtrs& scales, const ResidualPtrs& ef,
-                    int64_t rows, int64_t n, int K, int bits, float ef_beta, hipStream_t stream);
+                    const CodePtrs& codes, const ScalePtrs& scales, const OffsetPtrs& offsets,
+                    const ResidualPtrs& ef, int64_t rows, int64_t n, int K, const QuantForm& form,
+                    hipStream_t stream);
+// mean_*: outputs of the second quantisation (requant != 0), each may be null.
 int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                                 float* u, const CodePtrs& codes, const ScalePtrs& scales,
-                                const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
-                                float ef_beta, float eta_out, float mu, int nesterov, int write_back,
-                                int requant, uint8_t* mean_codes, float* mean_scales,
-                                hipStream_t stream);
+                                const OffsetPtrs& offsets, const ResidualPtrs& ef, int64_t rows,
+                                int64_t n, int K, const QuantForm& form, float eta_out, float mu,
+                                int nesterov, int write_back, int requant, uint8_t* mean_codes,
+                                float* mean_scales, float* mean_offsets, hipStream_t stream);
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
-                         float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                         int64_t n, int K, int bits, float eta_out, float mu, int nesterov,
+                         float* u, const CodePtrs& codes, const ScalePtrs& scales,
+                         const OffsetPtrs& offsets, int64_t rows, int64_t n, int K,
+                         const QuantForm& form, float eta_out, float mu, int nesterov,
                          int write_back, hipStream_t stream);
 
 }  // namespace mlc

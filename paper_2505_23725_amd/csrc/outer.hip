@@ -1,8 +1,9 @@
 // HBM-bound kernels of the DiLoCo outer step (paper Sec. 4.1 eqs. 2-3, Algorithm 1 lines
 // after the inner loop, Algorithm 2 "compress parameter delta"):
 //   * fused pseudogradient / K-way average / outer Nesterov / write-back,
-//   * row-wise 2/4/8-bit linear quantiser of theta_g - theta_k (IEEE fp32, ties to even),
-//     optionally with error feedback (Algorithm 2, EF branch),
+//   * 2/4/8-bit linear quantiser of theta_g - theta_k (IEEE fp32, ties to even), range per row
+//     or per matrix, with or without an offset, optionally with error feedback (Algorithm 2,
+//     EF branch) and a second quantisation of the mean,
 //   * dequantise + K-way average + outer update + write-back.
 // The K worker replicas live on this GPU, so the average is a loop over K pointers
 // in a fixed order: ((d_1 + d_2) + ...) * (1/K).
@@ -97,16 +98,35 @@ __global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
   }
 }
 
-// ---- row-wise linear quantiser (Sec. 2 "Compressed Communication"; Algorithm 2) --------
-// bits = 2, 4 or 8: levels -qmax..qmax with qmax = 2^(bits-1) - 1, code = level + 2^(bits-1),
-// 8 / bits codes per byte with the lowest column in the lowest bits.  With error feedback
-// the value quantised is e = fl32(fl32(beta * E) + delta) and the residual becomes
-// E <- fl32(e - level * scale); both are fixed in fp32 (no fused multiply-add) so that codes
-// and residuals are reproducible bit for bit.
-__device__ __forceinline__ int quant_level(float v, float scale, float qmax) {
-  float q = rintf(v / scale);               // IEEE division, round half to even
-  q = fminf(fmaxf(q, -qmax), qmax);
+// ---- linear quantiser (Sec. 2 "Compressed Communication"; Algorithm 2) -----------------
+// bits = 2, 4 or 8.  Without offset: levels -L..L, L = 2^(bits-1) - 1, over [-amax, amax],
+// stored code = level + 2^(bits-1).  With offset: levels 0..L, L = 2^bits - 1, over
+// [min, max], stored as they are, dequantised value = level * scale + min.  8 / bits codes
+// per byte, the lowest column in the lowest bits.  The range is taken per row, or per matrix
+// (then it has been computed beforehand and is read from the scale / offset arrays).  With
+// error feedback the value quantised is e = fl32(fl32(beta * E) + delta) and the residual
+// becomes E <- fl32(e - dequantised value).  Every operation is a single fp32 operation
+// (no fused multiply-add) so that codes and residuals are reproducible bit for bit.
+struct Range { float scale, lo; };
+
+__device__ __forceinline__ Range make_range(float mn, float mx, const QuantForm& f) {
+  Range r;
+  if (f.offset) { r.lo = mn; r.scale = __fsub_rn(mx, mn) / f.levels; }
+  else { r.lo = 0.f; r.scale = fmaxf(mx, -mn) / f.levels; }
+  return r;
+}
+
+__device__ __forceinline__ int quant_level(float v, const Range& r, const QuantForm& f) {
+  if (!(r.scale > 0.f)) return 0;
+  const float x = f.offset ? __fsub_rn(v, r.lo) : v;
+  float q = rintf(x / r.scale);             // IEEE division, round half to even
+  q = fminf(fmaxf(q, f.offset ? 0.f : -f.levels), f.levels);
   return (int)q;
+}
+
+__device__ __forceinline__ float dequant_level(int q, const Range& r, const QuantForm& f) {
+  const float s = __fmul_rn((float)q, r.scale);
+  return f.offset ? __fadd_rn(s, r.lo) : s;
 }
 
 __device__ __forceinline__ float ef_input(float delta, float residual, float beta) {
@@ -114,83 +134,181 @@ __device__ __forceinline__ float ef_input(float delta, float residual, float bet
 }
 
 // 8 adjacent levels of a row, first column c (a multiple of 8) <-> bits bytes of its codes
-__device__ __forceinline__ void store_codes8(uint8_t* crow, int c, const int (&q)[8], int bits) {
+__device__ __forceinline__ void store_codes8(uint8_t* crow, int c, const int (&q)[8], int bits, int bias) {
   if (bits == 4) {
     unsigned int p = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + 8) << (4 * j);
+    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + bias) << (4 * j);
     *reinterpret_cast<unsigned int*>(crow + c / 2) = p;
   } else if (bits == 8) {
     u32x2 p = {0u, 0u};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      p.x |= (unsigned int)(q[j] + 128) << (8 * j);
-      p.y |= (unsigned int)(q[j + 4] + 128) << (8 * j);
+      p.x |= (unsigned int)(q[j] + bias) << (8 * j);
+      p.y |= (unsigned int)(q[j + 4] + bias) << (8 * j);
     }
     *reinterpret_cast<u32x2*>(crow + c) = p;
   } else {
     unsigned int p = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + 2) << (2 * j);
+    for (int j = 0; j < 8; ++j) p |= (unsigned int)(q[j] + bias) << (2 * j);
     *reinterpret_cast<unsigned short*>(crow + c / 4) = (unsigned short)p;
   }
 }
 
-__device__ __forceinline__ void load_levels8(const uint8_t* crow, int c, int (&q)[8], int bits) {
+__device__ __forceinline__ void load_levels8(const uint8_t* crow, int c, int (&q)[8], int bits, int bias) {
   if (bits == 4) {
     const unsigned int p = *reinterpret_cast<const unsigned int*>(crow + c / 2);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (4 * j)) & 0xfu) - 8;
+    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (4 * j)) & 0xfu) - bias;
   } else if (bits == 8) {
     const u32x2 p = *reinterpret_cast<const u32x2*>(crow + c);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      q[j] = (int)((p.x >> (8 * j)) & 0xffu) - 128;
-      q[j + 4] = (int)((p.y >> (8 * j)) & 0xffu) - 128;
+      q[j] = (int)((p.x >> (8 * j)) & 0xffu) - bias;
+      q[j + 4] = (int)((p.y >> (8 * j)) & 0xffu) - bias;
     }
   } else {
     const unsigned int p = *reinterpret_cast<const unsigned short*>(crow + c / 4);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (2 * j)) & 0x3u) - 2;
+    for (int j = 0; j < 8; ++j) q[j] = (int)((p >> (2 * j)) & 0x3u) - bias;
   }
 }
 
-// Two passes over the row (absmax, then codes), one wavefront per row, all K workers; the
+// Range of worker k's row (or of the matrix the row belongs to) as stored by an earlier pass.
+__device__ __forceinline__ Range stored_range(const ScalePtrs& scales, const OffsetPtrs& offsets, int k,
+                                              long grp, const QuantForm& f) {
+  Range r;
+  r.scale = scales.p[k][grp];
+  r.lo = f.offset ? offsets.p[k][grp] : 0.f;
+  return r;
+}
+
+// ---- ranges per matrix (the "global" scope): init, reduce with atomics, finalise --------
+// Floats are ordered through an order-preserving map to unsigned keys, so that the
+// reduction is exact and independent of the order in which workgroups arrive.
+__device__ __forceinline__ unsigned int float_key(float v) {
+  const unsigned int b = __float_as_uint(v);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(unsigned int k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+__global__ void matrix_range_init_kernel(ScalePtrs scales, OffsetPtrs offsets, long count, int offset) {
+  const long b = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int k = blockIdx.y;
+  if (b >= count) return;
+  reinterpret_cast<unsigned int*>(scales.p[k])[b] = 0u;                    // below every key
+  if (offset) reinterpret_cast<unsigned int*>(offsets.p[k])[b] = 0xffffffffu;   // above every key
+}
+
+template <typename WT, typename GT, bool VEC>
+__global__ __launch_bounds__(OT_THREADS) void matrix_range_kernel(
+    WorkerPtrs w, const GT* __restrict__ theta_g, ScalePtrs scales, OffsetPtrs offsets, ResidualPtrs ef,
+    long elems, QuantForm form) {
+  __shared__ float red[2][OT_THREADS / 64];
+  const long b = blockIdx.y;
+  const int k = blockIdx.z;
+  const GT* tg = theta_g + b * elems;
+  const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + b * elems;
+  const float* res = ef.p[k] ? ef.p[k] + b * elems : nullptr;
+  constexpr int W = VEC ? 8 : 1;
+  float mn = INFINITY, mx = -INFINITY;
+  for (long i = ((long)blockIdx.x * OT_THREADS + threadIdx.x) * W; i < elems;
+       i += (long)gridDim.x * OT_THREADS * W) {
+    float a[8], c[8], e[8];
+    if (VEC) {
+      Ld<GT>::load8(tg + i, a); Ld<WT>::load8(tk + i, c);
+      if (res) Ld<float>::load8(res + i, e);
+    } else {
+      a[0] = Ld<GT>::load1(tg + i); c[0] = Ld<WT>::load1(tk + i);
+      if (res) e[0] = res[i];
+    }
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+      const float d = a[j] - c[j];
+      const float v = res ? ef_input(d, e[j], form.ef_beta) : d;
+      mn = fminf(mn, v); mx = fmaxf(mx, v);
+    }
+  }
+  mn = wave_min(mn); mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mn; red[1][threadIdx.x >> 6] = mx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mn = fminf(fminf(red[0][0], red[0][1]), fminf(red[0][2], red[0][3]));
+    mx = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    if (mn <= mx) {          // this workgroup saw at least one element
+      if (form.offset) {
+        atomicMax(reinterpret_cast<unsigned int*>(scales.p[k]) + b, float_key(mx));
+        atomicMin(reinterpret_cast<unsigned int*>(offsets.p[k]) + b, float_key(mn));
+      } else {               // amax >= 0: its bit pattern is ordered like an unsigned
+        atomicMax(reinterpret_cast<unsigned int*>(scales.p[k]) + b, __float_as_uint(fmaxf(mx, -mn)));
+      }
+    }
+  }
+}
+
+__global__ void matrix_range_finish_kernel(ScalePtrs scales, OffsetPtrs offsets, long count, QuantForm form) {
+  const long b = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int k = blockIdx.y;
+  if (b >= count) return;
+  if (form.offset) {
+    const float mx = key_float(reinterpret_cast<unsigned int*>(scales.p[k])[b]);
+    const float mn = key_float(reinterpret_cast<unsigned int*>(offsets.p[k])[b]);
+    const Range r = make_range(mn, mx, form);
+    scales.p[k][b] = r.scale;
+    offsets.p[k][b] = r.lo;
+  } else {
+    scales.p[k][b] = scales.p[k][b] / form.levels;     // the array holds amax
+  }
+}
+
+// Two passes over the row (range, then codes), one wavefront per row, all K workers; the
 // second pass re-reads data the first pass just pulled through L2.  Rows whose length is
 // not a multiple of 8 go one code byte (8 / bits columns) per lane and step.
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
-    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, ResidualPtrs ef,
-    long rows, int n, int K, int bits, float qmax, float ef_beta) {
+    WorkerPtrs w, const GT* __restrict__ theta_g, CodePtrs codes, ScalePtrs scales, OffsetPtrs offsets,
+    ResidualPtrs ef, long rows, int n, int K, QuantForm form) {
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * (OT_THREADS / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const GT* tg = theta_g + row * n;
+  const int bits = form.bits;
   const int W = VEC ? 8 : 8 / bits;         // elements per lane per step
   const long row_bytes = (long)n * bits / 8;
   for (int k = 0; k < K; ++k) {
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + row * n;
     float* res = ef.p[k] ? ef.p[k] + row * n : nullptr;
-    float amax = 0.f;
-    for (int c = lane * W; c < n; c += 64 * W) {
-      float a[8], b[8], e[8];
-      if (VEC) {
-        Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
-        if (res) Ld<float>::load8(res + c, e);
-      } else {
+    Range rg;
+    if (form.rows_per_range) {
+      rg = stored_range(scales, offsets, k, row / form.rows_per_range, form);
+    } else {
+      float mn = INFINITY, mx = -INFINITY;
+      for (int c = lane * W; c < n; c += 64 * W) {
+        float a[8], b[8], e[8];
+        if (VEC) {
+          Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
+          if (res) Ld<float>::load8(res + c, e);
+        } else {
+          for (int j = 0; j < W; ++j) {
+            a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
+            if (res) e[j] = res[c + j];
+          }
+        }
         for (int j = 0; j < W; ++j) {
-          a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
-          if (res) e[j] = res[c + j];
+          const float d = a[j] - b[j];
+          const float v = res ? ef_input(d, e[j], form.ef_beta) : d;
+          mn = fminf(mn, v); mx = fmaxf(mx, v);
         }
       }
-      for (int j = 0; j < W; ++j) {
-        const float d = a[j] - b[j];
-        amax = fmaxf(amax, fabsf(res ? ef_input(d, e[j], ef_beta) : d));
+      rg = make_range(wave_min(mn), wave_max(mx), form);
+      if (lane == 0) {
+        scales.p[k][row] = rg.scale;
+        if (form.offset) offsets.p[k][row] = rg.lo;
       }
     }
-    amax = wave_max(amax);
-    const float scale = amax / qmax;
-    if (lane == 0) scales.p[k][row] = scale;
     uint8_t* crow = codes.p[k] + row * row_bytes;
     for (int c = lane * W; c < n; c += 64 * W) {
       float a[8], b[8], e[8];
@@ -206,16 +324,16 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
       int q[8];
       for (int j = 0; j < W; ++j) {
         const float d = a[j] - b[j];
-        const float v = res ? ef_input(d, e[j], ef_beta) : d;
-        q[j] = (amax > 0.f) ? quant_level(v, scale, qmax) : 0;
-        e[j] = __fsub_rn(v, __fmul_rn((float)q[j], scale));
+        const float v = res ? ef_input(d, e[j], form.ef_beta) : d;
+        q[j] = quant_level(v, rg, form);
+        e[j] = __fsub_rn(v, dequant_level(q[j], rg, form));
       }
       if (VEC) {
-        store_codes8(crow, c, q, bits);
+        store_codes8(crow, c, q, bits, form.code_bias);
         if (res) Ld<float>::store8(res + c, e);
       } else {
         unsigned int p = 0;
-        for (int j = 0; j < W; ++j) p |= (unsigned int)(q[j] + (1 << (bits - 1))) << (bits * j);
+        for (int j = 0; j < W; ++j) p |= (unsigned int)(q[j] + form.code_bias) << (bits * j);
         crow[c / W] = (uint8_t)p;
         if (res)
           for (int j = 0; j < W; ++j) res[c + j] = e[j];
@@ -228,21 +346,24 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
 // and keeps it in registers (NV vectors of 8 elements per thread), so theta_g is read once
 // for all K workers and every theta_k exactly once.  Same arithmetic as above.  With
 // OUTER the dequantised values go straight into the mean and eq. 3 without re-reading
-// theta_g or the codes; codes and scales are written either way.
+// theta_g or the codes; codes, scales and offsets are written either way.
 template <typename WT, typename GT, int NV, int G, bool OUTER>
 __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
     WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
-    ResidualPtrs ef, long rows, int n, int K, int bits, float qmax, float ef_beta, float eta,
-    float mu, float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes,
-    float* mean_scales) {
+    OffsetPtrs offsets, ResidualPtrs ef, long rows, int n, int K, QuantForm form, float eta, float mu,
+    float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes, float* mean_scales,
+    float* mean_offsets) {
   constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
-  __shared__ float red[2][OT_THREADS / 64];
-  __shared__ float red2[OT_THREADS / 64];
+  constexpr int NW = OT_THREADS / 64;
+  __shared__ float red[2][2][NW];          // [parity of k][min, max][wavefront]
+  __shared__ float red2[2][NW];
   const int t = threadIdx.x % G;
   const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
   const bool live = row < rows;            // whole groups are live or not; no early return
   const long rbase = live ? row * n : 0;   // (the workgroup-wide barrier below needs everyone)
+  const int bits = form.bits;
   const long row_bytes = (long)n * bits / 8;
+  const long grp = form.rows_per_range ? (live ? row / form.rows_per_range : 0) : (live ? row : 0);
   float tg[NV][8], acc[OUTER ? NV : 1][8];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -259,7 +380,7 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
     float* res = ef.p[k] ? ef.p[k] + rbase : nullptr;
     float d[NV][8];
-    float amax = 0.f;
+    float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
@@ -272,23 +393,32 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
           float e[8];
           Ld<float>::load8(res + c, e);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) d[i][j] = ef_input(d[i][j], e[j], ef_beta);
+          for (int j = 0; j < 8; ++j) d[i][j] = ef_input(d[i][j], e[j], form.ef_beta);
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(d[i][j]));
+        for (int j = 0; j < 8; ++j) { mn = fminf(mn, d[i][j]); mx = fmaxf(mx, d[i][j]); }
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) d[i][j] = 0.f;
       }
     }
-    amax = wave_max(amax);
-    if constexpr (G > 64) {
-      if ((threadIdx.x & 63) == 0) red[k & 1][threadIdx.x >> 6] = amax;
-      __syncthreads();
-      amax = fmaxf(fmaxf(red[k & 1][0], red[k & 1][1]), fmaxf(red[k & 1][2], red[k & 1][3]));
+    Range rg;
+    if (form.rows_per_range) {
+      rg = stored_range(scales, offsets, k, grp, form);
+    } else {
+      mn = wave_min(mn); mx = wave_max(mx);
+      if constexpr (G > 64) {
+        if ((threadIdx.x & 63) == 0) { red[k & 1][0][threadIdx.x >> 6] = mn; red[k & 1][1][threadIdx.x >> 6] = mx; }
+        __syncthreads();
+        mn = fminf(fminf(red[k & 1][0][0], red[k & 1][0][1]), fminf(red[k & 1][0][2], red[k & 1][0][3]));
+        mx = fmaxf(fmaxf(red[k & 1][1][0], red[k & 1][1][1]), fmaxf(red[k & 1][1][2], red[k & 1][1][3]));
+      }
+      rg = make_range(mn, mx, form);
+      if (live && t == 0) {
+        scales.p[k][row] = rg.scale;
+        if (form.offset) offsets.p[k][row] = rg.lo;
+      }
     }
-    const float scale = amax / qmax;
-    if (live && t == 0) scales.p[k][row] = scale;
     uint8_t* crow = codes.p[k] + row * row_bytes;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -298,12 +428,12 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
         float e[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          q[j] = (amax > 0.f) ? quant_level(d[i][j], scale, qmax) : 0;
-          const float sent = __fmul_rn((float)q[j], scale);
+          q[j] = quant_level(d[i][j], rg, form);
+          const float sent = dequant_level(q[j], rg, form);
           e[j] = __fsub_rn(d[i][j], sent);
           if constexpr (OUTER) acc[i][j] += sent;
         }
-        store_codes8(crow, c, q, bits);
+        store_codes8(crow, c, q, bits, form.code_bias);
         if (res) Ld<float>::store8(res + c, e);
       }
     }
@@ -316,19 +446,26 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
     if (requant) {
       // Second quantisation (the dequantise-reduce-quantise step between the two modelled
       // collectives): Psi is quantised row-wise again and its dequantised value is used.
-      float amax = 0.f;
+      float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < NV; ++i)
+      for (int i = 0; i < NV; ++i) {
+        const int c = (t + i * G) * 8;
+        if (live && c < n)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(acc[i][j]));    // dead lanes hold 0
-      amax = wave_max(amax);
-      if constexpr (G > 64) {
-        if ((threadIdx.x & 63) == 0) red2[threadIdx.x >> 6] = amax;
-        __syncthreads();
-        amax = fmaxf(fmaxf(red2[0], red2[1]), fmaxf(red2[2], red2[3]));
+          for (int j = 0; j < 8; ++j) { mn = fminf(mn, acc[i][j]); mx = fmaxf(mx, acc[i][j]); }
       }
-      const float scale = amax / qmax;
-      if (mean_scales && live && t == 0) mean_scales[row] = scale;
+      mn = wave_min(mn); mx = wave_max(mx);
+      if constexpr (G > 64) {
+        if ((threadIdx.x & 63) == 0) { red2[0][threadIdx.x >> 6] = mn; red2[1][threadIdx.x >> 6] = mx; }
+        __syncthreads();
+        mn = fminf(fminf(red2[0][0], red2[0][1]), fminf(red2[0][2], red2[0][3]));
+        mx = fmaxf(fmaxf(red2[1][0], red2[1][1]), fmaxf(red2[1][2], red2[1][3]));
+      }
+      const Range rg = make_range(mn, mx, form);
+      if (live && t == 0) {
+        if (mean_scales) mean_scales[row] = rg.scale;
+        if (mean_offsets && form.offset) mean_offsets[row] = rg.lo;
+      }
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int c = (t + i * G) * 8;
@@ -336,10 +473,10 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
           int q[8];
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            q[j] = (amax > 0.f) ? quant_level(acc[i][j], scale, qmax) : 0;
-            acc[i][j] = __fmul_rn((float)q[j], scale);
+            q[j] = quant_level(acc[i][j], rg, form);
+            acc[i][j] = dequant_level(q[j], rg, form);
           }
-          if (mean_codes) store_codes8(mean_codes + row * row_bytes, c, q, bits);
+          if (mean_codes) store_codes8(mean_codes + row * row_bytes, c, q, bits, form.code_bias);
         }
       }
     }
@@ -364,7 +501,9 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
-    long rows, int n, int K, int bits, float eta, float mu, float inv_k, int nesterov, int write_back) {
+    OffsetPtrs offsets, long rows, int n, int K, QuantForm form, float eta, float mu, float inv_k,
+    int nesterov, int write_back) {
+  const int bits = form.bits;
   const int W = VEC ? 8 : 8 / bits;
   const int per_row = n / W;
   const long items = rows * per_row;
@@ -374,6 +513,7 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     const long row = i / per_row;
     const int c = (int)(i - row * per_row) * W;
     const long off = row * n + c;
+    const long grp = form.rows_per_range ? row / form.rows_per_range : row;
     float tg[8], uv[8], acc[8];
     if (VEC) { Ld<GT>::load8(theta_g + off, tg); Ld<float>::load8(u + off, uv); }
     else
@@ -381,18 +521,18 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int k = 0; k < K; ++k) {
-      const float sc = scales.p[k][row];
+      const Range rg = stored_range(scales, offsets, k, grp, form);
       const uint8_t* crow = codes.p[k] + row * row_bytes;
       int q[8];
       if (VEC) {
-        load_levels8(crow, c, q, bits);
+        load_levels8(crow, c, q, bits, form.code_bias);
       } else {
         const unsigned int p = crow[c / W];
-        for (int j = 0; j < W; ++j) q[j] = (int)((p >> (bits * j)) & ((1u << bits) - 1u)) - (1 << (bits - 1));
+        for (int j = 0; j < W; ++j) q[j] = (int)((p >> (bits * j)) & ((1u << bits) - 1u)) - form.code_bias;
       }
-      for (int j = 0; j < W; ++j) acc[j] += __fmul_rn((float)q[j], sc);
+      for (int j = 0; j < W; ++j) acc[j] += dequant_level(q[j], rg, form);
     }
-    for (int j = 0; j < W; ++j) outer_update<GT>(tg[j], uv[j], acc[j] * inv_k, eta, mu, nesterov);
+    for (int j = 0; j < W; ++j) outer_update<GT>(tg[j], uv[j], __fmul_rn(acc[j], inv_k), eta, mu, nesterov);
     if (VEC) {
       Ld<GT>::store8(theta_g + off, tg);
       Ld<float>::store8(u + off, uv);
@@ -447,21 +587,64 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
 }
 
 namespace {
-float quant_qmax(int bits) { return (float)((1 << (bits - 1)) - 1); }
 bool has_residuals(const ResidualPtrs& ef) { return ef.p[0] != nullptr; }
 }  // namespace
 
+QuantForm make_quant_form(int bits, int offset, int64_t rows_per_range, float ef_beta) {
+  QuantForm f;
+  f.bits = bits;
+  f.offset = offset ? 1 : 0;
+  f.rows_per_range = (int)rows_per_range;
+  f.levels = offset ? (float)((1 << bits) - 1) : (float)((1 << (bits - 1)) - 1);
+  f.code_bias = offset ? 0 : (1 << (bits - 1));
+  f.ef_beta = ef_beta;
+  return f;
+}
+
+int launch_matrix_ranges(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
+                         const ScalePtrs& scales, const OffsetPtrs& offsets, const ResidualPtrs& ef,
+                         int64_t count, int64_t m, int64_t n, int K, const QuantForm& form,
+                         hipStream_t stream) {
+  if (count > 65535 || K > 65535) return MLC_ERR_SHAPE;
+  const long elems = m * n;
+  const bool vec = elems % 8 == 0;
+  const int nblk = cap_blocks((elems / (vec ? 8 : 1) + OT_THREADS - 1) / OT_THREADS, 512);
+  const double bytes = (double)count * elems * (K * esize(worker_dtype) + K * esize(global_dtype) +
+                                                (has_residuals(ef) ? 4.0 * K : 0.0));
+  LaunchScope scope(MLC_KERNEL_QUANTIZE, stream, 0.0, bytes);
+  const dim3 small((unsigned)((count + 255) / 256), (unsigned)K);
+  hipLaunchKernelGGL(matrix_range_init_kernel, small, dim3(256), 0, stream, scales, offsets, (long)count,
+                     form.offset);
+#define MLC_CALL(WT, GT)                                                                          \
+  do {                                                                                            \
+    if (vec)                                                                                      \
+      hipLaunchKernelGGL((matrix_range_kernel<WT, GT, true>), dim3(nblk, (unsigned)count, K),      \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, scales, offsets, ef,  \
+                         elems, form);                                                            \
+    else                                                                                          \
+      hipLaunchKernelGGL((matrix_range_kernel<WT, GT, false>), dim3(nblk, (unsigned)count, K),     \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, scales, offsets, ef,  \
+                         elems, form);                                                            \
+  } while (0)
+  MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
+#undef MLC_CALL
+  hipLaunchKernelGGL(matrix_range_finish_kernel, small, dim3(256), 0, stream, scales, offsets, (long)count,
+                     form);
+  return check_launch();
+}
+
 int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, int global_dtype,
-                    const CodePtrs& codes, const ScalePtrs& scales, const ResidualPtrs& ef,
-                    int64_t rows, int64_t n, int K, int bits, float ef_beta, hipStream_t stream) {
+                    const CodePtrs& codes, const ScalePtrs& scales, const OffsetPtrs& offsets,
+                    const ResidualPtrs& ef, int64_t rows, int64_t n, int K, const QuantForm& form,
+                    hipStream_t stream) {
   const long blocks = (rows + OT_THREADS / 64 - 1) / (OT_THREADS / 64);
   if (blocks > 0x7fffffffL) return MLC_ERR_SHAPE;
+  const int bits = form.bits;
   const double bytes = (double)rows * n * (K * esize(worker_dtype) + esize(global_dtype) + bits / 8.0 * K +
                                            (has_residuals(ef) ? 8.0 * K : 0.0)) +
                        (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_QUANTIZE, stream, 0.0, bytes);
   const bool vec = n % 8 == 0;
-  const float qmax = quant_qmax(bits);
   // single-pass register kernel: a wavefront per row up to 2048 columns, a workgroup per row
   // up to 24576; otherwise (or for odd row lengths) the two-pass kernel
   if (vec && n <= 24576 && !(worker_dtype == MLC_F32 && global_dtype == MLC_BF16)) {
@@ -473,8 +656,8 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
 #define MLC_QR(WT, GT, NV, G)                                                                     \
   hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, false>), dim3((unsigned)nblk),       \
                      dim3(OT_THREADS), 0, stream, w, (GT*)const_cast<void*>(theta_g), (float*)nullptr, \
-                     codes, scales, ef, (long)rows, (int)n, K, bits, qmax, ef_beta, 0.f, 0.f, 0.f, 0, 0, 0, \
-                     (uint8_t*)nullptr, (float*)nullptr)
+                     codes, scales, offsets, ef, (long)rows, (int)n, K, form, 0.f, 0.f, 0.f, 0, 0, 0, \
+                     (uint8_t*)nullptr, (float*)nullptr, (float*)nullptr)
 #define MLC_QR_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QR(WT, GT, 1, 64); else if (nv == 2) MLC_QR(WT, GT, 2, 64);   \
@@ -493,12 +676,12 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
   do {                                                                                            \
     if (vec)                                                                                      \
       hipLaunchKernelGGL((quantize_rows_kernel<WT, GT, true>), dim3((unsigned)blocks),            \
-                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, ef,   \
-                         (long)rows, (int)n, K, bits, qmax, ef_beta);                             \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales,       \
+                         offsets, ef, (long)rows, (int)n, K, form);                               \
     else                                                                                          \
       hipLaunchKernelGGL((quantize_rows_kernel<WT, GT, false>), dim3((unsigned)blocks),           \
-                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales, ef,   \
-                         (long)rows, (int)n, K, bits, qmax, ef_beta);                             \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, codes, scales,       \
+                         offsets, ef, (long)rows, (int)n, K, form);                               \
   } while (0)
   MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
 #undef MLC_CALL
@@ -506,10 +689,12 @@ int launch_quantize(const WorkerPtrs& w, int worker_dtype, const void* theta_g, 
 }
 
 int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
-                         float* u, const CodePtrs& codes, const ScalePtrs& scales, int64_t rows,
-                         int64_t n, int K, int bits, float eta_out, float mu, int nesterov,
+                         float* u, const CodePtrs& codes, const ScalePtrs& scales,
+                         const OffsetPtrs& offsets, int64_t rows, int64_t n, int K,
+                         const QuantForm& form, float eta_out, float mu, int nesterov,
                          int write_back, hipStream_t stream) {
   const bool vec = n % 8 == 0;
+  const int bits = form.bits;
   const long items = rows * (n / (vec ? 8 : 8 / bits));
   const int blocks = cap_blocks((items + OT_THREADS - 1) / OT_THREADS, 256 * 16);
   const double bytes = (double)rows * n * (bits / 8.0 * K + 2 * esize(global_dtype) + 8 +
@@ -521,12 +706,12 @@ int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, i
   do {                                                                                            \
     if (vec)                                                                                      \
       hipLaunchKernelGGL((dequant_outer_kernel<WT, GT, true>), dim3(blocks), dim3(OT_THREADS), 0, \
-                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K, bits,  \
-                         eta_out, mu, inv_k, nesterov, write_back);                               \
+                         stream, w, (GT*)theta_g, u, codes, scales, offsets, (long)rows, (int)n,  \
+                         K, form, eta_out, mu, inv_k, nesterov, write_back);                      \
     else                                                                                          \
       hipLaunchKernelGGL((dequant_outer_kernel<WT, GT, false>), dim3(blocks), dim3(OT_THREADS), 0,\
-                         stream, w, (GT*)theta_g, u, codes, scales, (long)rows, (int)n, K, bits,  \
-                         eta_out, mu, inv_k, nesterov, write_back);                               \
+                         stream, w, (GT*)theta_g, u, codes, scales, offsets, (long)rows, (int)n,  \
+                         K, form, eta_out, mu, inv_k, nesterov, write_back);                      \
   } while (0)
   MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
 #undef MLC_CALL
@@ -537,10 +722,10 @@ int launch_dequant_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, i
 // caller then runs the quantiser and the dequantising update as two launches).
 int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype,
                                 float* u, const CodePtrs& codes, const ScalePtrs& scales,
-                                const ResidualPtrs& ef, int64_t rows, int64_t n, int K, int bits,
-                                float ef_beta, float eta_out, float mu, int nesterov, int write_back,
-                                int requant, uint8_t* mean_codes, float* mean_scales,
-                                hipStream_t stream) {
+                                const OffsetPtrs& offsets, const ResidualPtrs& ef, int64_t rows,
+                                int64_t n, int K, const QuantForm& form, float eta_out, float mu,
+                                int nesterov, int write_back, int requant, uint8_t* mean_codes,
+                                float* mean_scales, float* mean_offsets, hipStream_t stream) {
   if (n % 8 || n > 16384 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
     return MLC_ERR_UNSUPPORTED;
   const int g = n <= 2048 ? 64 : OT_THREADS;
@@ -549,18 +734,18 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
   const long rpb = OT_THREADS / g;
   const long nblk = (rows + rpb - 1) / rpb;
   if (nblk > 0x7fffffffL) return MLC_ERR_SHAPE;
+  const int bits = form.bits;
   const double bytes = (double)rows * n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + bits / 8.0 * K +
                                            (has_residuals(ef) ? 8.0 * K : 0.0) +
                                            (mean_codes ? bits / 8.0 : 0.0) +
                                            2 * esize(global_dtype) + 8) + (double)rows * 4 * K;
   LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
   const float inv_k = 1.0f / (float)K;
-  const float qmax = quant_qmax(bits);
 #define MLC_QO(WT, GT, NV, G)                                                                     \
   hipLaunchKernelGGL((quantize_rows_reg_kernel<WT, GT, NV, G, true>), dim3((unsigned)nblk),        \
-                     dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, ef, (long)rows, \
-                     (int)n, K, bits, qmax, ef_beta, eta_out, mu, inv_k, nesterov, write_back, requant, \
-                     mean_codes, mean_scales)
+                     dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, codes, scales, offsets, ef,  \
+                     (long)rows, (int)n, K, form, eta_out, mu, inv_k, nesterov, write_back, requant, \
+                     mean_codes, mean_scales, mean_offsets)
 #define MLC_QO_NV(WT, GT)                                                                         \
   do {                                                                                            \
     if (g == 64) { if (nv == 1) MLC_QO(WT, GT, 1, 64); else if (nv == 2) MLC_QO(WT, GT, 2, 64);   \

@@ -148,6 +148,12 @@ def test_outer_step_argument_errors():
     assert call(group(), second_quantisation=2, quant_bits=4) == -5
     assert call(group(n=20480), second_quantisation=1, quant_bits=4) == -7
     assert call(group(n=12), second_quantisation=1, quant_bits=4) == -7
+    # other forms of the quantiser need a compressor; the offset form needs the offsets
+    assert call(group(), quant_offset=1) == -5
+    assert call(group(), quant_per_matrix=1) == -5
+    assert call(group(), quant_offset=2, quant_bits=4) == -5
+    assert call(group(), quant_offset=1, quant_bits=4) == -1
+    assert call(group(), quant_per_matrix=1, second_quantisation=1, quant_bits=4) == -7
     null_res = (C.c_void_p * K)(0x9000, None)
     assert call(group(residuals=C.cast(null_res, C.POINTER(C.c_void_p))), error_feedback=1, quant_bits=4,
                 ef_beta=1.0) == -1

@@ -198,3 +198,80 @@ def test_second_quantisation_bit_exact(cnt, m, n, K, wd, gd, bits, ef):
     mlc.muloco_outer_step([mlc.OuterGroup([w.to(DEV) for w in ws0], tg2, u2, c2, s2, res2)], hp)
     torch.cuda.synchronize()
     assert torch.equal(tg2, tg) and torch.equal(u2, u)
+
+
+FORM_CASES = [
+    # cnt, m, n, K, worker dtype, global dtype, bits, offset, per matrix, error feedback, second quantisation
+    (2, 64, 128, 3, torch.bfloat16, torch.float32, 4, True, False, False, False),
+    (1, 50, 1000, 2, torch.bfloat16, torch.float32, 4, True, False, True, False),
+    (1, 9, 12, 2, torch.float32, torch.float32, 4, True, False, False, False),        # byte path
+    (1, 12, 5120, 2, torch.bfloat16, torch.bfloat16, 8, True, False, False, True),
+    (1, 24, 768, 4, torch.bfloat16, torch.float32, 2, True, False, True, True),
+    (1, 5, 24584, 1, torch.bfloat16, torch.float32, 4, True, False, False, False),    # two-pass quantiser
+    (3, 64, 128, 3, torch.bfloat16, torch.float32, 4, False, True, False, False),
+    (2, 50, 1000, 2, torch.bfloat16, torch.float32, 4, True, True, True, False),
+    (2, 9, 13, 2, torch.float32, torch.float32, 8, False, True, False, False),        # scalar range pass
+    (2, 6, 20480, 2, torch.bfloat16, torch.float32, 4, True, True, False, False),     # two launches after the ranges
+    (4, 40, 2560, 4, torch.bfloat16, torch.bfloat16, 2, False, True, True, False),
+]
+
+
+@pytest.mark.parametrize("cnt,m,n,K,wd,gd,bits,offset,per_matrix,ef,second", FORM_CASES)
+def test_quantiser_forms_bit_exact(cnt, m, n, K, wd, gd, bits, offset, per_matrix, ef, second):
+    seed = 13 * n + K + bits + 2 * offset + per_matrix
+    tg0, ws0, u0 = _inputs(cnt, m, n, K, wd, gd, seed)
+    if per_matrix and cnt > 1:      # matrices of different magnitude: their ranges must differ
+        for k in range(K):
+            ws0[k][1] = (tg0[1].float() - 8 * (tg0[1].float() - ws0[k][1].float())).to(wd)
+    tg, u = tg0.to(DEV), u0.to(DEV)
+    ws = [w.to(DEV) for w in ws0]
+    ranges = cnt if per_matrix else cnt * m
+    codes = [torch.full((cnt * m, n * bits // 8), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(K)]
+    scales = [torch.full((ranges,), -1.0, dtype=torch.float32, device=DEV) for _ in range(K)]
+    offsets = [torch.full((ranges,), -1.0, dtype=torch.float32, device=DEV) for _ in range(K)] if offset else None
+    res0 = [S.normal((cnt, m, n), 1e-3, seed, 40 + k) for k in range(K)] if ef else None
+    res = [r.to(DEV) for r in res0] if ef else None
+    mcodes = torch.full((cnt * m, n * bits // 8), 0xAA, dtype=torch.uint8, device=DEV) if second else None
+    mscales = torch.full((cnt * m,), -1.0, dtype=torch.float32, device=DEV) if second else None
+    moffsets = torch.full((cnt * m,), -1.0, dtype=torch.float32, device=DEV) if second and offset else None
+    grp = mlc.OuterGroup(ws, tg, u, codes, scales, res, mcodes, mscales, offsets, moffsets)
+    hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, quant_bits=bits, error_feedback=ef, ef_beta=0.9,
+                          second_quantisation=second, quant_offset=offset, quant_per_matrix=per_matrix)
+    ref = diloco.outer_step(to_f64(tg0).reshape(-1, n), to_f64(u0).reshape(-1, n),
+                            [to_f64(w).reshape(-1, n) for w in ws0], eta_out=0.9, mu=0.8, quant_bits=bits,
+                            residuals=[r.numpy().reshape(-1, n) for r in res0] if ef else None, ef_beta=0.9,
+                            second_quantisation=second, quant_offset=offset,
+                            quant_scope="matrix" if per_matrix else "row", rows_per_matrix=m)
+    pack = diloco.pack_codes_unsigned if offset else diloco.pack_codes
+
+    def check_compressor(codes_, scales_, offsets_, res_):
+        for k in range(K):
+            got, want = codes_[k].cpu().numpy(), pack(ref["q"][k], bits)
+            assert np.array_equal(got, want), f"worker {k}: {(got != want).sum()} code bytes differ"
+            assert _same_bits(scales_[k].cpu().numpy(), ref["scales"][k]), f"worker {k}: scales differ"
+            if offset:
+                assert _same_bits(offsets_[k].cpu().numpy(), ref["offsets"][k]), f"worker {k}: offsets differ"
+            if ef:
+                assert _same_bits(res_[k].cpu().numpy().reshape(-1, n), ref["residuals"][k]), f"worker {k}: residuals"
+
+    if not second:      # the compressor alone, on copies of what it updates
+        c2 = [c.clone() for c in codes]
+        s2 = [x.clone() for x in scales]
+        o2 = [x.clone() for x in offsets] if offset else None
+        r2 = [r.clone() for r in res] if ef else None
+        mlc.muloco_quantize_delta([mlc.OuterGroup(ws, tg, u, c2, s2, r2, None, None, o2)], hp)
+        torch.cuda.synchronize()
+        assert torch.equal(tg.cpu(), tg0) and torch.equal(u.cpu(), u0)
+        check_compressor(c2, s2, o2, r2)
+    mlc.muloco_outer_step([grp], hp)
+    torch.cuda.synchronize()
+    check_compressor(codes, scales, offsets, res)
+    if second:
+        assert np.array_equal(mcodes.cpu().numpy(), pack(ref["mean_q"], bits)), "second-stage codes differ"
+        assert _same_bits(mscales.cpu().numpy(), ref["mean_scales"])
+        if offset:
+            assert _same_bits(moffsets.cpu().numpy(), ref["mean_offsets"])
+    assert_fp32_close(u.cpu().reshape(-1, n), ref["u"], "outer momentum")
+    assert_stored_close(tg.cpu().reshape(-1, n), ref["theta"], "global parameters")
+    for k in range(K):
+        assert torch.equal(ws[k].cpu(), tg.cpu().to(wd)), f"worker {k} write-back differs from theta_g"
