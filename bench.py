@@ -185,6 +185,21 @@ def main() -> int:
         del groups
         torch.cuda.empty_cache()
 
+    # The same step replayed from a HIP graph (one submission per step instead of one per
+    # kernel): what launch overhead costs on the small workloads.
+    graph_ms = None
+    try:
+        graph = MulocoJob.capture(step)
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.steps
+        del graph
+    except Exception as e:          # the eager figures stand without it
+        graph_ms = f"failed: {e}"
+
     ms_per_step = wall * 1e3 / args.steps
     gemm = timing["ns_gemm"]
     ns_tflops = gemm["flops"] / (gemm["total_ms"] * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
@@ -203,6 +218,7 @@ def main() -> int:
         "ns_flop_per_step": gemm["flops"] / args.steps,
         "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
         "quantize_outer_fused": fam("dequant_outer"),
+        "graph_replay_ms_per_step": graph_ms,
         "quantize_standalone_whole_model": quant_alone,
         "quantised_outer_step_whole_model_variants": variants,
         "nominal_ns_tflops_equivalent": None,

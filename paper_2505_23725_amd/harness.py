@@ -196,6 +196,26 @@ class MulocoJob:
     def outer_step(self, quant_bits: int = 0) -> None:
         B.muloco_outer_step(self.outer_groups(quant=quant_bits != 0), self.outer_hparams(quant_bits))
 
+    @staticmethod
+    def capture(fn):
+        """Record the kernel launches of fn() into a HIP graph and return it (replay()
+        re-issues them with one call).  The library's entry points only enqueue kernels on
+        the current stream, neither allocating nor synchronising, so they can be captured;
+        fn runs once eagerly first (its effects are real) so that one-time set-up such as
+        raising a kernel's LDS limit happens outside the capture.  The timing recorder must
+        be off: it records events."""
+        B.muloco_timing_enable(False)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        return graph
+
     def ns_flops(self, iters: int = 5) -> float:
         """Nominal Newton-Schulz FLOP (4 s^2 l + 2 s^3 per iteration) of one replica's inner step."""
         tot = 0.0

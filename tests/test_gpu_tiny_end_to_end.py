@@ -53,3 +53,44 @@ def test_tiny_workload_h8_then_outer_step():
         assert rel_fro(th_gpu - th0.reshape(-1, n), out["theta"] - th0.reshape(-1, n)) <= NS_TOL
         assert torch.equal(job.workers[0][gi], job.theta_g[gi]), "write-back must copy theta_g"
     print(f"tiny workload: worst displacement error after H={wl.H} steps {worst:.3e}")
+
+
+def test_graph_replay_equals_eager_steps():
+    """The whole step (Muon inner step, outer step, 4-bit quantised outer step per layer) is
+    captured into a HIP graph once; replays, with eager work and synchronisations between
+    them, must give the bits that the same number of eager steps gives."""
+    import paper_2505_23725_amd as mlc
+    from paper_2505_23725_amd.harness import MulocoJob
+    wl = S.WORKLOADS["tiny"]
+
+    def make():
+        job = MulocoJob(wl, generate_on="cpu", seed=3, K=2, with_quant=True)
+        job.draw_gradients(0)
+        hp = job.outer_hparams(quant_bits=4)
+
+        def step():
+            job.inner_step()
+            job.outer_step(0)
+            for layer in range(wl.layers):
+                mlc.muloco_outer_step(job.layer_fragment(layer, quant=True), hp)
+        return job, step
+
+    eager, eager_step = make()
+    replayed, replayed_step = make()
+    graph = MulocoJob.capture(replayed_step)      # runs the step once eagerly, then records it
+    eager_step()
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 16, device="cuda:0")
+    for rep in range(3):
+        eager_step()
+        graph.replay()
+        scratch.add_(1.0)                          # unrelated eager work between replays
+        torch.cuda.synchronize()
+        for gi in range(len(eager.shapes)):
+            assert torch.equal(eager.theta_g[gi], replayed.theta_g[gi]), f"replay {rep}: theta_g of group {gi}"
+            assert torch.equal(eager.u[gi], replayed.u[gi]), f"replay {rep}: outer momentum of group {gi}"
+            assert torch.equal(eager.W[gi], replayed.W[gi]) and torch.equal(eager.M[gi], replayed.M[gi])
+            for k in range(eager.K):
+                assert torch.equal(eager.codes[k][gi], replayed.codes[k][gi])
+                assert torch.equal(eager.scales[k][gi], replayed.scales[k][gi])
+    assert float(scratch[0]) == 3.0
