@@ -217,6 +217,36 @@ int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups,
                           const mlc_outer_hparams* hp, void* stream);
 
 /* ------------------------------------------------------------------------------------
+ * AdamW step for the parameters Muon does not cover: embeddings, norms, biases (paper
+ * Sec. 4, "AdamW inner updates and induced pseudogradient"; Sec. 2 "Muon" applies Muon to
+ * the hidden matrices only).  Per element, in fp32:
+ *     m     <- beta1 * m + (1 - beta1) * g
+ *     v     <- beta2 * v + (1 - beta2) * g * g
+ *     theta <- theta - lr * m^ / (sqrt(v^) + eps) - lr * weight_decay * theta
+ * with m^ = m, v^ = v as printed, or m^ = m / (1 - beta1^step), v^ = v / (1 - beta2^step)
+ * when bias_correction = 1 (step counts from 1).  Tensors are flat; every pointer is a
+ * device pointer aligned to 16 bytes; m and v are fp32 and updated in place.
+ */
+typedef struct {
+  int64_t count;          /* number of elements                                        */
+  void* param;            /* theta, in/out                                             */
+  int param_dtype;        /* mlc_dtype                                                 */
+  const void* grad;       /* g                                                         */
+  int grad_dtype;         /* mlc_dtype                                                 */
+  float* exp_avg;         /* m, in/out                                                 */
+  float* exp_avg_sq;      /* v, in/out                                                 */
+} mlc_adamw_group;
+
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int bias_correction;    /* 0: as printed ; 1: divide by 1 - beta^step                 */
+  int step;               /* 1-based step count, used only with bias_correction        */
+} mlc_adamw_hparams;
+
+int muloco_adamw_step(const mlc_adamw_group* groups, int n_groups, const mlc_adamw_hparams* hp,
+                      void* stream);
+
+/* ------------------------------------------------------------------------------------
  * Optional timing recorder (for benchmarks; not part of the method).
  *
  * While enabled, every kernel launch of this library is bracketed by HIP events on the
@@ -233,7 +263,8 @@ enum {
   MLC_KERNEL_QUANTIZE = 5,    /* row-wise quantiser (stand-alone compressor)           */
   MLC_KERNEL_DEQUANT_OUTER = 6,/* (quantise +) dequantise + average + outer update     */
   MLC_KERNEL_CONVERT = 7,     /* layout / dtype conversion around newton_schulz        */
-  MLC_KERNEL_FAMILIES = 8
+  MLC_KERNEL_ADAMW = 8,       /* AdamW step of the non-matrix parameters               */
+  MLC_KERNEL_FAMILIES = 9
 };
 typedef struct {
   int64_t launches;      /* launches recorded since the last read                      */

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     library, library_path, strerror,
     newton_schulz, newton_schulz_workspace_bytes, newton_schulz_workspace_min_bytes,
     muloco_inner_step, muloco_inner_workspace_bytes, muloco_inner_workspace_min_bytes,
-    muloco_outer_step, muloco_quantize_delta,
+    muloco_outer_step, muloco_quantize_delta, muloco_adamw_step, AdamWHParams,
     muloco_timing_enable, muloco_timing_read, KERNEL_FAMILIES,
 )

@@ -11,7 +11,7 @@ import torch
 MLC_F32, MLC_BF16 = 0, 1
 MLC_MAX_WORKERS = 32
 KERNEL_FAMILIES = ["ns_gemm", "momentum", "norm", "update", "outer", "quantize",
-                   "dequant_outer", "convert"]
+                   "dequant_outer", "convert", "adamw"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmuloco.so")
@@ -57,6 +57,17 @@ class _OuterHParams(C.Structure):
                 ("quant_per_matrix", C.c_int)]
 
 
+class _AdamWGroup(C.Structure):
+    _fields_ = [("count", C.c_int64), ("param", C.c_void_p), ("param_dtype", C.c_int),
+                ("grad", C.c_void_p), ("grad_dtype", C.c_int),
+                ("exp_avg", C.c_void_p), ("exp_avg_sq", C.c_void_p)]
+
+
+class _AdamWHParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("bias_correction", C.c_int), ("step", C.c_int)]
+
+
 class _KernelTiming(C.Structure):
     _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -97,6 +108,8 @@ def library() -> C.CDLL:
         f = getattr(lib, name)
         f.restype = C.c_int
         f.argtypes = [C.POINTER(_OuterGroup), C.c_int, C.POINTER(_OuterHParams), C.c_void_p]
+    lib.muloco_adamw_step.restype = C.c_int
+    lib.muloco_adamw_step.argtypes = [C.POINTER(_AdamWGroup), C.c_int, C.POINTER(_AdamWHParams), C.c_void_p]
     lib.muloco_timing_enable.restype = C.c_int
     lib.muloco_timing_enable.argtypes = [C.c_int]
     lib.muloco_timing_read.restype = C.c_int
@@ -368,6 +381,33 @@ def muloco_quantize_delta(groups: Sequence[OuterGroup], hp: OuterHParams, stream
     rc = library().muloco_quantize_delta(_outer_array(groups), len(groups), C.byref(chp),
                                          _stream(stream))
     _check(rc, "muloco_quantize_delta")
+
+
+@dataclass
+class AdamWHParams:
+    lr: float
+    beta1: float = 0.9
+    beta2: float = 0.95
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    bias_correction: bool = False
+    step: int = 1
+
+
+def muloco_adamw_step(tensors: Sequence[tuple], hp: AdamWHParams, stream=None) -> None:
+    """tensors: (param, grad, exp_avg, exp_avg_sq) tuples of equally sized device tensors."""
+    arr = (_AdamWGroup * max(1, len(tensors)))()
+    for i, (p_, g_, m_, v_) in enumerate(tensors):
+        n = p_.numel()
+        if g_.numel() != n or m_.numel() != n or v_.numel() != n:
+            raise ValueError("param, grad, exp_avg and exp_avg_sq must have the same size")
+        if m_.dtype != torch.float32 or v_.dtype != torch.float32:
+            raise TypeError("exp_avg and exp_avg_sq must be float32")
+        arr[i] = _AdamWGroup(n, _dev_ptr(p_, "param"), _dtype_code(p_), _dev_ptr(g_, "grad"), _dtype_code(g_),
+                             _dev_ptr(m_, "exp_avg"), _dev_ptr(v_, "exp_avg_sq"))
+    chp = _AdamWHParams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, int(hp.bias_correction), int(hp.step))
+    rc = library().muloco_adamw_step(arr, len(tensors), C.byref(chp), _stream(stream))
+    _check(rc, "muloco_adamw_step")
 
 
 def muloco_timing_enable(on: bool) -> None:

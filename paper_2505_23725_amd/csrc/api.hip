@@ -1,5 +1,6 @@
 // C-ABI entry points, host-side argument validation, launch planning and the optional
 // timing recorder.  Nothing here allocates device memory or synchronises the stream.
+#include <cmath>
 #include <mutex>
 #include <vector>
 
@@ -472,6 +473,39 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
                               g.count * g.m * g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
                               hp->write_back, stream);
     }
+    if (rc != MLC_OK) return rc;
+  }
+  return MLC_OK;
+}
+
+int muloco_adamw_step(const mlc_adamw_group* groups, int n_groups, const mlc_adamw_hparams* hp,
+                      void* stream_) {
+  if (!groups || !hp) return MLC_ERR_NULL;
+  if (n_groups < 0) return MLC_ERR_ARG;
+  if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
+      !(hp->eps >= 0.f) || !(hp->weight_decay >= 0.f))
+    return MLC_ERR_ARG;
+  if (hp->bias_correction != 0 && hp->bias_correction != 1) return MLC_ERR_ARG;
+  if (hp->bias_correction && hp->step < 1) return MLC_ERR_ARG;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_adamw_group& g = groups[i];
+    if (!g.param || !g.grad || !g.exp_avg || !g.exp_avg_sq) return MLC_ERR_NULL;
+    if (!valid_dtype(g.param_dtype) || !valid_dtype(g.grad_dtype)) return MLC_ERR_DTYPE;
+    if (g.count < 1 || g.count > ((int64_t)1 << 40)) return MLC_ERR_SHAPE;
+    if (!aligned16(g.param) || !aligned16(g.grad) || !aligned16(g.exp_avg) || !aligned16(g.exp_avg_sq))
+      return MLC_ERR_ARG;
+  }
+  float c1 = 1.f, c2 = 1.f;
+  if (hp->bias_correction) {
+    c1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
+    c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)hp->beta2, (double)hp->step)));
+  }
+  hipStream_t stream = (hipStream_t)stream_;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_adamw_group& g = groups[i];
+    const int rc = launch_adamw(g.param, g.param_dtype, g.grad, g.grad_dtype, g.exp_avg, g.exp_avg_sq,
+                                g.count, hp->lr, hp->beta1, hp->beta2, hp->eps,
+                                hp->lr * hp->weight_decay, c1, c2, stream);
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;

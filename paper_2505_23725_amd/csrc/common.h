@@ -92,6 +92,10 @@ int launch_param_update(void* W, int dtype, const bf16_t* O, const float* oscale
 int launch_ns_store(const bf16_t* X, const float* oscale, void* out, int dtype, int64_t count,
                     int64_t m, int64_t n, int64_t mp, int64_t ldx, hipStream_t stream);
 
+int launch_adamw(void* theta, int param_dtype, const void* grad, int grad_dtype, float* m, float* v,
+                 int64_t n, float lr, float b1, float b2, float eps, float decay, float c1, float c2,
+                 hipStream_t stream);
+
 // ---- outer step kernels (outer.hip) ----------------------------------------------
 struct WorkerPtrs { void* p[MLC_MAX_WORKERS]; };
 struct CodePtrs { uint8_t* p[MLC_MAX_WORKERS]; };

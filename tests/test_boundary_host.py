@@ -169,3 +169,27 @@ def test_binding_rejects_cpu_tensors_and_bad_dtypes():
         mlc.newton_schulz(x, x, torch.zeros(16, dtype=torch.uint8))
     with pytest.raises(TypeError):
         B._dtype_code(torch.zeros(2, dtype=torch.float16))
+
+
+def test_adamw_argument_errors():
+    lib = mlc.library()
+
+    def call(g=None, **hpkw):
+        d = dict(count=16, param=0x1000, param_dtype=0, grad=0x2000, grad_dtype=0, exp_avg=0x3000,
+                 exp_avg_sq=0x4000)
+        d.update(g or {})
+        h = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, bias_correction=0, step=1)
+        h.update(hpkw)
+        arr = (B._AdamWGroup * 1)(B._AdamWGroup(**d))
+        hp = B._AdamWHParams(**h)
+        return lib.muloco_adamw_step(arr, 1, C.byref(hp), None)
+
+    assert call(dict(param=None)) == -1
+    assert call(dict(exp_avg_sq=None)) == -1
+    assert call(dict(count=0)) == -2
+    assert call(dict(grad_dtype=5)) == -3
+    assert call(dict(grad=0x2004)) == -5             # misaligned
+    assert call(beta1=1.0) == -5
+    assert call(lr=-1.0) == -5
+    assert call(bias_correction=1, step=0) == -5
+    assert lib.muloco_adamw_step(None, 0, None, None) == -1
