@@ -39,6 +39,12 @@ with Nesterov momentum) and Algorithm 2's "compress parameter delta" branch.  Re
       code  = q_j (unsigned);  dequantised value = fl32(fl32(float(q_j) * scale) + lo).
 * Scope: "row" takes the range over each row, "matrix" over each whole matrix (the paper's
   global variant, one range per parameter tensor); scale and lo are then stored per matrix.
+* Top-k sparsification (Sec. 2 "Compressed Communication"): of each weight matrix the
+  fraction f of entries with the largest magnitude is kept, the others are set to zero; each
+  worker sparsifies once and the sparse tensors are averaged (an all-gather in the paper).
+  Reading: the number kept is k = ceil(f * m * n), at least 1; the threshold tau is the k-th
+  largest magnitude of the fp32 values and every entry with |v| >= tau is kept, so entries
+  that tie with the k-th one are all kept and the result does not depend on any order.
 """
 import numpy as np
 
@@ -163,6 +169,27 @@ def error_feedback_compress(theta_g_f32, theta_k_f32, residual_f32, beta, bits=4
     return q, scale, (e - sent).astype(np.float32)
 
 
+def topk_count(fraction, elems):
+    """k = ceil(fraction * elems) in double precision, clamped to [1, elems]."""
+    import math
+    return int(min(elems, max(1, math.ceil(float(fraction) * float(elems)))))
+
+
+def topk_sparsify(values_f32, fraction, rows_per_matrix):
+    """Top-k by magnitude within each matrix of a 2-D float32 array [count * m, n].
+
+    Returns (sparse float32 array, thresholds float32 [count])."""
+    v = np.asarray(values_f32, dtype=np.float32)
+    rows, n = v.shape
+    assert rows % rows_per_matrix == 0
+    g = v.reshape(rows // rows_per_matrix, rows_per_matrix * n)
+    k = topk_count(fraction, g.shape[1])
+    mag = np.abs(g)
+    tau = np.sort(mag, axis=1)[:, g.shape[1] - k].astype(np.float32)     # k-th largest
+    kept = np.where(mag >= tau[:, None], g, np.float32(0)).astype(np.float32)
+    return kept.reshape(v.shape), tau
+
+
 def pack_codes(q, bits):
     """Signed levels -> packed bytes: code = q + 2^(bits-1), 8 / bits codes per byte, the
     lowest column of a byte's group in its lowest bits."""
@@ -226,7 +253,7 @@ def requantize_mean(sent_f32, bits=4):
 
 def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bits=0,
                residuals=None, ef_beta=1.0, second_quantisation=False, quant_offset=False,
-               quant_scope="row", rows_per_matrix=None):
+               quant_scope="row", rows_per_matrix=None, topk_fraction=None):
     """One outer step on one 2-D tensor [rows, n].
 
     theta_g, thetas[k]: stored values (float64 holding fp32/bf16-representable numbers).
@@ -256,6 +283,22 @@ def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bit
             out["q"].append(q.astype(np.int8) if not quant_offset else q)
             out["scales"].append(s)
             out["offsets"].append(lo)
+            deltas.append(sent.astype(np.float64))
+    elif topk_fraction is not None:
+        out["thresholds"] = []
+        if residuals is not None:
+            out["residuals"] = []
+        tg32 = theta_g.astype(np.float32)
+        for k, th in enumerate(thetas):
+            tk32 = np.asarray(th, np.float64).astype(np.float32)
+            v = (tg32 - tk32).astype(np.float32)
+            if residuals is not None:      # Algorithm 2, EF branch
+                E = np.asarray(residuals[k], dtype=np.float32)
+                v = ((np.float32(ef_beta) * E).astype(np.float32) + v).astype(np.float32)
+            sent, tau = topk_sparsify(v, topk_fraction, rows_per_matrix)
+            if residuals is not None:
+                out["residuals"].append((v - sent).astype(np.float32))
+            out["thresholds"].append(tau)
             deltas.append(sent.astype(np.float64))
     else:
         assert residuals is None, "error feedback needs a compressor"
