@@ -185,6 +185,31 @@ def main() -> int:
         del groups
         torch.cuda.empty_cache()
 
+    # Top-k sparsified outer step (5 % kept, error feedback) over the whole model: four selection
+    # passes and the sparsified update; the figure is algorithmic bytes of all five passes.
+    topk_fig = None
+    if job.K * n_elems * 4 + (1 << 30) < torch.cuda.mem_get_info()[0]:
+        groups = []
+        for gi, (c, m, n) in enumerate(job.shapes):
+            g = mlc.OuterGroup([job.workers[k][gi] for k in range(job.K)], job.theta_g[gi], job.u[gi])
+            g.residuals = [torch.zeros((c, m, n), dtype=torch.float32, device="cuda:0") for _ in range(job.K)]
+            groups.append(g)
+        hpt = job.outer_hparams(error_feedback=True, ef_beta=0.9)
+        wsp = torch.empty(mlc.muloco_topk_workspace_bytes(groups, job.K), dtype=torch.uint8, device="cuda:0")
+        mlc.muloco_topk_outer_step(groups, hpt, 0.05, wsp)
+        torch.cuda.synchronize()
+        mlc.muloco_timing_enable(True)
+        mlc.muloco_timing_read()
+        for _ in range(2):
+            mlc.muloco_topk_outer_step(groups, hpt, 0.05, wsp)
+        torch.cuda.synchronize()
+        tt = mlc.muloco_timing_read()["topk"]
+        mlc.muloco_timing_enable(False)
+        gbs = tt["bytes"] / (tt["total_ms"] * 1e-3) * 1e-9 if tt["total_ms"] > 0 else 0.0
+        topk_fig = {"ms": tt["total_ms"] / 2, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        del groups, wsp
+        torch.cuda.empty_cache()
+
     # AdamW on a tensor the size of an embedding plus an output layer (2 x 32768 x d_model), the
     # kind of parameter Muon does not cover; outside the timed region.
     adamw_fig = None
@@ -246,6 +271,7 @@ def main() -> int:
         "quantize_outer_fused": fam("dequant_outer"),
         "graph_replay_ms_per_step": graph_ms,
         "adamw_embedding_sized_tensor": adamw_fig,
+        "topk_5pct_error_feedback_outer_step_whole_model": topk_fig,
         "quantize_standalone_whole_model": quant_alone,
         "quantised_outer_step_whole_model_variants": variants,
         "nominal_ns_tflops_equivalent": None,

@@ -217,6 +217,27 @@ int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups,
                           const mlc_outer_hparams* hp, void* stream);
 
 /* ------------------------------------------------------------------------------------
+ * Outer step with top-k sparsification of the pseudogradients (paper Sec. 2 "Compressed
+ * Communication": the k% entries of a weight matrix with the largest magnitude are kept,
+ * the rest set to zero; sparsified once per worker, then averaged).
+ *
+ * For every worker k and every matrix [m][n] of a group, with N = m * n:
+ *     v     = Delta_k, or with error feedback fl32(fl32(ef_beta * E_k) + Delta_k)
+ *     kept  = ceil(fraction * N) (in double), at least 1, at most N
+ *     tau   = the kept-th largest |v| of the matrix
+ *     sent  = v where |v| >= tau, else 0      (entries that tie with tau are all kept)
+ *     E_k  <- v - sent                        (error feedback only)
+ * and the outer update of muloco_outer_step runs on the mean of the K sent tensors.
+ * hp->quant_bits must be 0.  If groups[i].scales is not NULL it receives tau: K device
+ * pointers to [count] floats.  workspace: device memory, 16-byte aligned, at least
+ * muloco_topk_workspace_bytes(groups, n_groups, hp->K) bytes; its contents need not be
+ * initialised and are not needed afterwards.
+ */
+size_t muloco_topk_workspace_bytes(const mlc_outer_group* groups, int n_groups, int K);
+int muloco_topk_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
+                           double fraction, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
  * AdamW step for the parameters Muon does not cover: embeddings, norms, biases (paper
  * Sec. 4, "AdamW inner updates and induced pseudogradient"; Sec. 2 "Muon" applies Muon to
  * the hidden matrices only).  Per element, in fp32:
@@ -264,7 +285,8 @@ enum {
   MLC_KERNEL_DEQUANT_OUTER = 6,/* (quantise +) dequantise + average + outer update     */
   MLC_KERNEL_CONVERT = 7,     /* layout / dtype conversion around newton_schulz        */
   MLC_KERNEL_ADAMW = 8,       /* AdamW step of the non-matrix parameters               */
-  MLC_KERNEL_FAMILIES = 9
+  MLC_KERNEL_TOPK = 9,        /* top-k selection passes + sparsified outer update      */
+  MLC_KERNEL_FAMILIES = 10
 };
 typedef struct {
   int64_t launches;      /* launches recorded since the last read                      */

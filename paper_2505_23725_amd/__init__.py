@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     newton_schulz, newton_schulz_workspace_bytes, newton_schulz_workspace_min_bytes,
     muloco_inner_step, muloco_inner_workspace_bytes, muloco_inner_workspace_min_bytes,
     muloco_outer_step, muloco_quantize_delta, muloco_adamw_step, AdamWHParams,
+    muloco_topk_outer_step, muloco_topk_workspace_bytes,
     muloco_timing_enable, muloco_timing_read, KERNEL_FAMILIES,
 )

@@ -11,7 +11,7 @@ import torch
 MLC_F32, MLC_BF16 = 0, 1
 MLC_MAX_WORKERS = 32
 KERNEL_FAMILIES = ["ns_gemm", "momentum", "norm", "update", "outer", "quantize",
-                   "dequant_outer", "convert", "adamw"]
+                   "dequant_outer", "convert", "adamw", "topk"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmuloco.so")
@@ -108,6 +108,11 @@ def library() -> C.CDLL:
         f = getattr(lib, name)
         f.restype = C.c_int
         f.argtypes = [C.POINTER(_OuterGroup), C.c_int, C.POINTER(_OuterHParams), C.c_void_p]
+    lib.muloco_topk_workspace_bytes.restype = C.c_size_t
+    lib.muloco_topk_workspace_bytes.argtypes = [C.POINTER(_OuterGroup), C.c_int, C.c_int]
+    lib.muloco_topk_outer_step.restype = C.c_int
+    lib.muloco_topk_outer_step.argtypes = [C.POINTER(_OuterGroup), C.c_int, C.POINTER(_OuterHParams),
+                                           C.c_double, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.muloco_adamw_step.restype = C.c_int
     lib.muloco_adamw_step.argtypes = [C.POINTER(_AdamWGroup), C.c_int, C.POINTER(_AdamWHParams), C.c_void_p]
     lib.muloco_timing_enable.restype = C.c_int
@@ -248,15 +253,19 @@ class OuterGroup:
             if self.outer_momentum.numel() != self.global_param.numel():
                 raise ValueError("outer momentum shape differs")
         cp = sp = None
-        if self.codes is not None or self.scales is not None:
-            if self.codes is None or self.scales is None or len(self.codes) != K or len(self.scales) != K:
-                raise ValueError("codes and scales must both hold K tensors")
-            for c_, s_ in zip(self.codes, self.scales):
+        if self.codes is not None:
+            if self.scales is None or len(self.codes) != K:
+                raise ValueError("codes need scales, K tensors each")
+            for c_ in self.codes:
                 if c_.dtype != torch.uint8 or c_.numel() not in [cnt * m * n * b // 8 for b in (2, 4, 8)]:
                     raise ValueError("codes[k] must be uint8 with count*m*n*bits/8 elements")
+            cp = (C.c_void_p * K)(*[_dev_ptr(c_, "codes[k]") for c_ in self.codes])
+        if self.scales is not None:      # quantiser scales, or the thresholds of the top-k step
+            if len(self.scales) != K:
+                raise ValueError("scales must hold K tensors")
+            for s_ in self.scales:
                 if s_.dtype != torch.float32 or s_.numel() not in (cnt * m, cnt):
                     raise ValueError("scales[k] must be float32 with count*m (or count) elements")
-            cp = (C.c_void_p * K)(*[_dev_ptr(c_, "codes[k]") for c_ in self.codes])
             sp = (C.c_void_p * K)(*[_dev_ptr(s_, "scales[k]") for s_ in self.scales])
         rp = None
         if self.residuals is not None:
@@ -381,6 +390,25 @@ def muloco_quantize_delta(groups: Sequence[OuterGroup], hp: OuterHParams, stream
     rc = library().muloco_quantize_delta(_outer_array(groups), len(groups), C.byref(chp),
                                          _stream(stream))
     _check(rc, "muloco_quantize_delta")
+
+
+def muloco_topk_workspace_bytes(groups: Sequence[OuterGroup], K: int) -> int:
+    return int(library().muloco_topk_workspace_bytes(_outer_array(groups), len(groups), int(K)))
+
+
+def muloco_topk_outer_step(groups: Sequence[OuterGroup], hp: OuterHParams, fraction: float,
+                           workspace: torch.Tensor, stream=None) -> None:
+    """Outer step on top-k sparsified pseudogradients; group.scales (K tensors of `count`
+    floats), if given, receive the thresholds."""
+    for g in groups:
+        if len(g.worker_params) != hp.K:
+            raise ValueError("every group needs K worker tensors")
+    if workspace.dtype != torch.uint8:
+        raise TypeError("workspace must be a uint8 tensor")
+    chp = hp._c()
+    rc = library().muloco_topk_outer_step(_outer_array(groups), len(groups), C.byref(chp), float(fraction),
+                                          _dev_ptr(workspace, "workspace"), workspace.numel(), _stream(stream))
+    _check(rc, "muloco_topk_outer_step")
 
 
 @dataclass

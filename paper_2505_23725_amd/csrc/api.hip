@@ -331,14 +331,15 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
 }
 
 static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
-                       bool need_update_state) {
+                       bool need_update_state, bool topk = false) {
   if (!hp || !groups) return MLC_ERR_NULL;
   if (n_groups < 0) return MLC_ERR_ARG;
   if (hp->K < 1 || hp->K > MLC_MAX_WORKERS) return MLC_ERR_ARG;
   if (hp->quant_bits != 0 && hp->quant_bits != 2 && hp->quant_bits != 4 && hp->quant_bits != 8)
     return MLC_ERR_ARG;
   if (hp->error_feedback != 0 && hp->error_feedback != 1) return MLC_ERR_ARG;
-  if (hp->error_feedback && (hp->quant_bits == 0 || !(hp->ef_beta >= 0.f))) return MLC_ERR_ARG;
+  if (topk && hp->quant_bits != 0) return MLC_ERR_ARG;
+  if (hp->error_feedback && ((hp->quant_bits == 0 && !topk) || !(hp->ef_beta >= 0.f))) return MLC_ERR_ARG;
   if (hp->second_quantisation != 0 && hp->second_quantisation != 1) return MLC_ERR_ARG;
   if (hp->second_quantisation && hp->quant_bits == 0) return MLC_ERR_ARG;
   if ((hp->quant_offset != 0 && hp->quant_offset != 1) ||
@@ -473,6 +474,54 @@ int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_out
                               g.count * g.m * g.n, hp->K, hp->eta_out, hp->mu, hp->nesterov,
                               hp->write_back, stream);
     }
+    if (rc != MLC_OK) return rc;
+  }
+  return MLC_OK;
+}
+
+size_t muloco_topk_workspace_bytes(const mlc_outer_group* groups, int n_groups, int K) {
+  if (!groups || n_groups < 0 || K < 1 || K > MLC_MAX_WORKERS) return 0;
+  size_t need = 0;
+  for (int i = 0; i < n_groups; ++i) {
+    if (groups[i].count < 1) return 0;
+    const size_t b = topk_workspace_bytes(groups[i].count, K);
+    if (b > need) need = b;
+  }
+  return need;
+}
+
+int muloco_topk_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
+                           double fraction, void* workspace, size_t workspace_bytes, void* stream_) {
+  int rc = check_outer(groups, n_groups, hp, true, true);
+  if (rc != MLC_OK) return rc;
+  if (!(fraction > 0.0) || fraction > 1.0) return MLC_ERR_ARG;
+  if (hp->second_quantisation || hp->quant_offset || hp->quant_per_matrix) return MLC_ERR_ARG;
+  if (n_groups == 0) return MLC_OK;
+  if (!workspace || ((uintptr_t)workspace & 15)) return MLC_ERR_WORKSPACE;
+  if (workspace_bytes < muloco_topk_workspace_bytes(groups, n_groups, hp->K)) return MLC_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_outer_group& g = groups[i];
+    if (g.count > 65535 || (double)g.m * (double)g.n >= 4294967296.0) return MLC_ERR_SHAPE;
+    if (g.scales)
+      for (int k = 0; k < hp->K; ++k)
+        if (!g.scales[k] || !aligned16(g.scales[k])) return MLC_ERR_ARG;
+  }
+  for (int i = 0; i < n_groups; ++i) {
+    const mlc_outer_group& g = groups[i];
+    WorkerPtrs w; ScalePtrs t; ResidualPtrs e;
+    for (int k = 0; k < MLC_MAX_WORKERS; ++k) {
+      w.p[k] = k < hp->K ? g.worker_params[k] : nullptr;
+      t.p[k] = (g.scales && k < hp->K) ? g.scales[k] : nullptr;
+      e.p[k] = (hp->error_feedback && k < hp->K) ? g.residuals[k] : nullptr;
+    }
+    const double elems = (double)g.m * (double)g.n;
+    double kc = std::ceil(fraction * elems);
+    if (kc < 1.0) kc = 1.0;
+    if (kc > elems) kc = elems;
+    rc = launch_topk_outer(w, g.worker_dtype, g.global_param, g.global_dtype, g.outer_momentum, e, t,
+                           g.count, g.m, g.n, hp->K, (unsigned int)kc, hp->ef_beta, hp->eta_out, hp->mu,
+                           hp->nesterov, hp->write_back, workspace, stream);
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;

@@ -105,6 +105,14 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
                        int write_back, hipStream_t stream);
 // residual (error-feedback) accumulators per worker; all null = no error feedback
 struct ResidualPtrs { float* p[MLC_MAX_WORKERS]; };
+// Radix-select state of one (worker, matrix) pair of the top-k sparsifier.
+struct TopkState { unsigned int hist[256]; unsigned int prefix, mask, rank, pad; };
+size_t topk_workspace_bytes(int64_t count, int K);
+// thresholds: per worker [count] floats (may be null): the k-th largest magnitude found.
+int launch_topk_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype, float* u,
+                      const ResidualPtrs& ef, const ScalePtrs& thresholds, int64_t count, int64_t m,
+                      int64_t n, int K, unsigned int kcount, float ef_beta, float eta_out, float mu,
+                      int nesterov, int write_back, void* workspace, hipStream_t stream);
 // Form of the linear quantiser (see muloco.h).
 struct QuantForm {
   int bits;              // 2, 4 or 8

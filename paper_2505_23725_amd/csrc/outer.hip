@@ -549,6 +549,152 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
   }
 }
 
+// ---- top-k sparsification (Sec. 2 "Compressed Communication") --------------------------
+// Of each matrix of each worker the k entries of largest magnitude are kept (all entries
+// that tie with the k-th one included).  The k-th largest magnitude is found exactly by a
+// radix select over the bit pattern of |v| (ordered like an unsigned for non-negative
+// floats): four passes of 8 bits, each a histogram of the entries that match the digits
+// found so far, then the digit in which the k-th entry falls.
+__global__ void topk_init_kernel(TopkState* st, unsigned int kcount) {
+  TopkState& s = st[blockIdx.x];
+  s.hist[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) { s.prefix = 0u; s.mask = 0u; s.rank = kcount; s.pad = 0u; }
+}
+
+template <typename WT, typename GT, bool VEC>
+__global__ __launch_bounds__(OT_THREADS) void topk_hist_kernel(
+    WorkerPtrs w, const GT* __restrict__ theta_g, ResidualPtrs ef, TopkState* st, long elems, int count,
+    int shift, float ef_beta) {
+  __shared__ unsigned int lh[OT_THREADS / 64][256];
+  const long b = blockIdx.y;
+  const int k = blockIdx.z;
+  TopkState& s = st[(long)k * count + b];
+  const unsigned int prefix = s.prefix, mask = s.mask;
+  for (int i = threadIdx.x; i < (OT_THREADS / 64) * 256; i += OT_THREADS) (&lh[0][0])[i] = 0u;
+  __syncthreads();
+  unsigned int* mine = lh[threadIdx.x >> 6];
+  const GT* tg = theta_g + b * elems;
+  const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + b * elems;
+  const float* res = ef.p[k] ? ef.p[k] + b * elems : nullptr;
+  constexpr int W = VEC ? 8 : 1;
+  unsigned int cur = 0xffffffffu, run = 0u;       // run-length of the current digit
+  for (long i = ((long)blockIdx.x * OT_THREADS + threadIdx.x) * W; i < elems;
+       i += (long)gridDim.x * OT_THREADS * W) {
+    float a[8], c[8], e[8];
+    if (VEC) {
+      Ld<GT>::load8(tg + i, a); Ld<WT>::load8(tk + i, c);
+      if (res) Ld<float>::load8(res + i, e);
+    } else {
+      a[0] = Ld<GT>::load1(tg + i); c[0] = Ld<WT>::load1(tk + i);
+      if (res) e[0] = res[i];
+    }
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+      const float d = a[j] - c[j];
+      const float v = res ? ef_input(d, e[j], ef_beta) : d;
+      const unsigned int key = __float_as_uint(fabsf(v));
+      if ((key & mask) == prefix) {
+        const unsigned int bin = (key >> shift) & 255u;
+        if (bin == cur) {
+          ++run;
+        } else {
+          if (run) atomicAdd(&mine[cur], run);
+          cur = bin; run = 1u;
+        }
+      }
+    }
+  }
+  if (run) atomicAdd(&mine[cur], run);
+  __syncthreads();
+  unsigned int tot = 0u;
+#pragma unroll
+  for (int wv = 0; wv < OT_THREADS / 64; ++wv) tot += lh[wv][threadIdx.x];
+  if (tot) atomicAdd(&s.hist[threadIdx.x], tot);
+}
+
+// The digit that holds the k-th largest entry: scan the histogram from the top.
+__global__ void topk_pick_kernel(TopkState* st, int shift) {
+  TopkState& s = st[blockIdx.x];
+  __shared__ unsigned int h[256];
+  h[threadIdx.x] = s.hist[threadIdx.x];
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned int above = 0u, rank = s.rank;
+    int bin = 255;
+    for (; bin > 0; --bin) {
+      if (above + h[bin] >= rank) break;
+      above += h[bin];
+    }
+    s.prefix |= (unsigned int)bin << shift;
+    s.mask |= 255u << shift;
+    s.rank = rank - above;
+  }
+  s.hist[threadIdx.x] = 0u;        // ready for the next pass
+}
+
+template <typename WT, typename GT, bool VEC>
+__global__ __launch_bounds__(OT_THREADS) void topk_outer_kernel(
+    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, ResidualPtrs ef, ScalePtrs thresholds,
+    const TopkState* st, long elems, int count, int K, float ef_beta, float eta, float mu, float inv_k,
+    int nesterov, int write_back) {
+  __shared__ unsigned int tau[MLC_MAX_WORKERS];
+  const long b = blockIdx.y;
+  if (threadIdx.x < K) {
+    tau[threadIdx.x] = st[(long)threadIdx.x * count + b].prefix;
+    if (blockIdx.x == 0 && thresholds.p[threadIdx.x])
+      thresholds.p[threadIdx.x][b] = __uint_as_float(tau[threadIdx.x]);
+  }
+  __syncthreads();
+  GT* tg = theta_g + b * elems;
+  float* ub = u + b * elems;
+  constexpr int W = VEC ? 8 : 1;
+  for (long i = ((long)blockIdx.x * OT_THREADS + threadIdx.x) * W; i < elems;
+       i += (long)gridDim.x * OT_THREADS * W) {
+    float a[8], uv[8], acc[8];
+    if (VEC) { Ld<GT>::load8(tg + i, a); Ld<float>::load8(ub + i, uv); }
+    else { a[0] = Ld<GT>::load1(tg + i); uv[0] = ub[i]; }
+#pragma unroll
+    for (int j = 0; j < W; ++j) acc[j] = 0.f;
+    for (int k = 0; k < K; ++k) {
+      const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + b * elems;
+      float* res = ef.p[k] ? ef.p[k] + b * elems : nullptr;
+      float c[8], e[8];
+      if (VEC) {
+        Ld<WT>::load8(tk + i, c);
+        if (res) Ld<float>::load8(res + i, e);
+      } else {
+        c[0] = Ld<WT>::load1(tk + i);
+        if (res) e[0] = res[i];
+      }
+#pragma unroll
+      for (int j = 0; j < W; ++j) {
+        const float d = a[j] - c[j];
+        const float v = res ? ef_input(d, e[j], ef_beta) : d;
+        const bool keep = __float_as_uint(fabsf(v)) >= tau[k];
+        acc[j] += keep ? v : 0.f;
+        e[j] = keep ? 0.f : v;           // what was not sent
+      }
+      if (res) {
+        if (VEC) Ld<float>::store8(res + i, e);
+        else res[i] = e[0];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < W; ++j) outer_update<GT>(a[j], uv[j], __fmul_rn(acc[j], inv_k), eta, mu, nesterov);
+    if (VEC) {
+      Ld<GT>::store8(tg + i, a);
+      Ld<float>::store8(ub + i, uv);
+      if (write_back)
+        for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a);
+    } else {
+      Ld<GT>::store1(tg + i, a[0]);
+      ub[i] = uv[0];
+      if (write_back)
+        for (int k = 0; k < K; ++k) Ld<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a[0]);
+    }
+  }
+}
+
 int check_launch() { return hipGetLastError() == hipSuccess ? MLC_OK : MLC_ERR_LAUNCH; }
 
 int cap_blocks(long blocks, long cap) {
@@ -758,6 +904,58 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
   else MLC_QO_NV(float, float);
 #undef MLC_QO_NV
 #undef MLC_QO
+  return check_launch();
+}
+
+size_t topk_workspace_bytes(int64_t count, int K) { return (size_t)count * K * sizeof(TopkState); }
+
+int launch_topk_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype, float* u,
+                      const ResidualPtrs& ef, const ScalePtrs& thresholds, int64_t count, int64_t m,
+                      int64_t n, int K, unsigned int kcount, float ef_beta, float eta_out, float mu,
+                      int nesterov, int write_back, void* workspace, hipStream_t stream) {
+  if (count > 65535) return MLC_ERR_SHAPE;
+  TopkState* st = (TopkState*)workspace;
+  const long elems = m * n;
+  const bool vec = elems % 8 == 0;
+  const int nblk = cap_blocks((elems / (vec ? 8 : 1) + OT_THREADS - 1) / OT_THREADS, 256);
+  const int n_states = (int)(count * K);
+  const double pass_bytes = (double)count * elems * (K * esize(worker_dtype) + K * esize(global_dtype) +
+                                                     (has_residuals(ef) ? 4.0 * K : 0.0));
+  const double last_bytes = (double)count * elems * (K * esize(worker_dtype) * (write_back ? 2 : 1) +
+                                                     (has_residuals(ef) ? 8.0 * K : 0.0) +
+                                                     2 * esize(global_dtype) + 8);
+  LaunchScope scope(MLC_KERNEL_TOPK, stream, 0.0, 4 * pass_bytes + last_bytes);
+  hipLaunchKernelGGL(topk_init_kernel, dim3(n_states), dim3(256), 0, stream, st, kcount);
+  for (int shift = 24; shift >= 0; shift -= 8) {
+#define MLC_CALL(WT, GT)                                                                          \
+  do {                                                                                            \
+    if (vec)                                                                                      \
+      hipLaunchKernelGGL((topk_hist_kernel<WT, GT, true>), dim3(nblk, (unsigned)count, K),         \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, ef, st, elems,       \
+                         (int)count, shift, ef_beta);                                             \
+    else                                                                                          \
+      hipLaunchKernelGGL((topk_hist_kernel<WT, GT, false>), dim3(nblk, (unsigned)count, K),        \
+                         dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, ef, st, elems,       \
+                         (int)count, shift, ef_beta);                                             \
+  } while (0)
+    MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
+#undef MLC_CALL
+    hipLaunchKernelGGL(topk_pick_kernel, dim3(n_states), dim3(256), 0, stream, st, shift);
+  }
+  const float inv_k = 1.0f / (float)K;
+#define MLC_CALL(WT, GT)                                                                          \
+  do {                                                                                            \
+    if (vec)                                                                                      \
+      hipLaunchKernelGGL((topk_outer_kernel<WT, GT, true>), dim3(nblk, (unsigned)count),           \
+                         dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, ef, thresholds, st, elems, \
+                         (int)count, K, ef_beta, eta_out, mu, inv_k, nesterov, write_back);       \
+    else                                                                                          \
+      hipLaunchKernelGGL((topk_outer_kernel<WT, GT, false>), dim3(nblk, (unsigned)count),          \
+                         dim3(OT_THREADS), 0, stream, w, (GT*)theta_g, u, ef, thresholds, st, elems, \
+                         (int)count, K, ef_beta, eta_out, mu, inv_k, nesterov, write_back);       \
+  } while (0)
+  MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
+#undef MLC_CALL
   return check_launch();
 }
 

@@ -193,3 +193,28 @@ def test_adamw_argument_errors():
     assert call(lr=-1.0) == -5
     assert call(bias_correction=1, step=0) == -5
     assert lib.muloco_adamw_step(None, 0, None, None) == -1
+
+
+def test_topk_argument_errors():
+    lib = mlc.library()
+    K = 2
+    wp = (C.c_void_p * K)(0x1000, 0x2000)
+
+    def call(frac=0.1, ws=0x10000, ws_bytes=1 << 20, g=None, **hpkw):
+        d = dict(count=3, m=4, n=16, worker_params=C.cast(wp, C.POINTER(C.c_void_p)), worker_dtype=1,
+                 global_param=0x3000, global_dtype=0, outer_momentum=0x4000)
+        d.update(g or {})
+        h = dict(K=K, eta_out=0.7, mu=0.9, nesterov=1, quant_bits=0, write_back=1)
+        h.update(hpkw)
+        arr = (B._OuterGroup * 1)(B._OuterGroup(**d))
+        hp = B._OuterHParams(**h)
+        return lib.muloco_topk_outer_step(arr, 1, C.byref(hp), C.c_double(frac), ws, ws_bytes, None)
+
+    assert call(frac=0.0) == -5 and call(frac=1.5) == -5 and call(frac=float("nan")) == -5
+    assert call(quant_bits=4) == -5                       # one compressor at a time
+    assert call(ws=None) == -4 and call(ws=0x10004) == -4 and call(ws_bytes=64) == -4
+    assert call(error_feedback=1, ef_beta=1.0) == -1      # residuals NULL
+    assert call(g=dict(global_param=None)) == -1
+    arr = (B._OuterGroup * 1)(B._OuterGroup(count=3, m=4, n=16))
+    assert lib.muloco_topk_workspace_bytes(arr, 1, K) == 3 * K * 260 * 4
+    assert lib.muloco_topk_workspace_bytes(arr, 1, 0) == 0

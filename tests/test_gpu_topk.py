@@ -1,0 +1,79 @@
+"""GPU parity: muloco_topk_outer_step (C-ABI) against the oracle: thresholds and residuals bit
+for bit, the outer update within the elementwise tolerances."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_23725_amd as mlc
+import synth_inputs as S
+from oracle import diloco
+from helpers import assert_fp32_close, assert_stored_close, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _inputs(cnt, m, n, K, wdtype, gdtype, seed):
+    tg = S.normal((cnt, m, n), S.PARAM_STD, seed, 0, dtype=gdtype)
+    ws = [(tg.float() - S.normal((cnt, m, n), S.DELTA_STD, seed, 10 + k)).to(wdtype) for k in range(K)]
+    u = S.normal((cnt, m, n), 1e-3, seed, 5, dtype=torch.float32)
+    return tg, ws, u
+
+
+CASES = [
+    # cnt, m, n, K, worker dtype, global dtype, fraction, error feedback
+    (2, 64, 128, 3, torch.bfloat16, torch.float32, 0.05, False),
+    (1, 50, 1000, 2, torch.bfloat16, torch.float32, 0.005, True),
+    (3, 33, 7, 2, torch.float32, torch.float32, 0.2, True),             # 231 elements: scalar path
+    (2, 96, 200, 4, torch.bfloat16, torch.bfloat16, 0.1, False),        # coarse grid of deltas: many ties
+    (2, 512, 2048, 2, torch.bfloat16, torch.float32, 0.01, True),
+    (1, 128, 128, 1, torch.float32, torch.float32, 1.0, False),         # everything is kept
+    (1, 128, 128, 2, torch.bfloat16, torch.float32, 1e-9, False),       # a single entry per matrix
+    (1, 40, 64, 2, torch.float32, torch.bfloat16, 0.5, True),
+]
+
+
+@pytest.mark.parametrize("cnt,m,n,K,wd,gd,frac,ef", CASES)
+def test_topk_outer_step_matches_oracle(cnt, m, n, K, wd, gd, frac, ef):
+    seed = 17 * n + K
+    tg0, ws0, u0 = _inputs(cnt, m, n, K, wd, gd, seed)
+    tg, u = tg0.to(DEV), u0.to(DEV)
+    ws = [w.to(DEV) for w in ws0]
+    res0 = [S.normal((cnt, m, n), 2e-3, seed, 40 + k) for k in range(K)] if ef else None
+    res = [r.to(DEV) for r in res0] if ef else None
+    taus = [torch.full((cnt,), -1.0, dtype=torch.float32, device=DEV) for _ in range(K)]
+    grp = mlc.OuterGroup(ws, tg, u, None, taus, res)
+    hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, error_feedback=ef, ef_beta=0.9)
+    need = mlc.muloco_topk_workspace_bytes([grp], K)
+    assert need == cnt * K * 260 * 4
+    wsp = torch.full((need,), 0xCD, dtype=torch.uint8, device=DEV)          # contents must not matter
+    mlc.muloco_topk_outer_step([grp], hp, frac, wsp)
+    torch.cuda.synchronize()
+    ref = diloco.outer_step(to_f64(tg0).reshape(-1, n), to_f64(u0).reshape(-1, n),
+                            [to_f64(w).reshape(-1, n) for w in ws0], eta_out=0.9, mu=0.8,
+                            residuals=[r.numpy().reshape(-1, n) for r in res0] if ef else None, ef_beta=0.9,
+                            topk_fraction=frac, rows_per_matrix=m)
+    for k in range(K):
+        assert np.array_equal(taus[k].cpu().numpy().view(np.uint32), ref["thresholds"][k].view(np.uint32)), \
+            f"worker {k}: thresholds differ"
+        if ef:
+            assert np.array_equal(res[k].cpu().numpy().reshape(-1, n).view(np.uint32),
+                                  ref["residuals"][k].view(np.uint32)), f"worker {k}: residuals differ"
+    assert_fp32_close(u.cpu().reshape(-1, n), ref["u"], "outer momentum")
+    assert_stored_close(tg.cpu().reshape(-1, n), ref["theta"], "global parameters")
+    for k in range(K):
+        assert torch.equal(ws[k].cpu(), tg.cpu().to(wd)), f"worker {k} write-back differs from theta_g"
+
+
+def test_topk_second_call_reuses_the_workspace():
+    cnt, m, n, K = 2, 64, 128, 2
+    tg0, ws0, u0 = _inputs(cnt, m, n, K, torch.bfloat16, torch.float32, 5)
+    hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, write_back=False)
+    wsp = torch.empty((cnt * K * 260 * 4,), dtype=torch.uint8, device=DEV)
+    outs = []
+    for _ in range(2):
+        tg, u = tg0.to(DEV), u0.to(DEV)
+        mlc.muloco_topk_outer_step([mlc.OuterGroup([w.to(DEV) for w in ws0], tg, u)], hp, 0.03, wsp)
+        torch.cuda.synchronize()
+        outs.append((tg.cpu(), u.cpu()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
