@@ -162,7 +162,7 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     Psi = fl32(((s_1 + s_2) + ... + s_K) * fl32(1 / K)),  s_k the dequantised values, fp32
  * is quantised row-wise again with the same bit width, and eq. 3 uses its dequantised
  * value.  Its codes and scales are written to mean_codes / mean_scales when these are not
- * NULL.  Rows longer than 16384 or not a multiple of 8 are MLC_ERR_UNSUPPORTED, and so are
+ * NULL.  Rows longer than 24576 or not a multiple of 8 are MLC_ERR_UNSUPPORTED, and so are
  * the pair of fp32 workers with a bf16 global copy and the per-matrix scope.
  * A "fragment" for streaming synchronisation is simply a call with a subset of groups.
  */

@@ -380,7 +380,7 @@ static int check_outer(const mlc_outer_group* groups, int n_groups, const mlc_ou
       if ((g.mean_codes && !aligned16(g.mean_codes)) || (g.mean_scales && !aligned16(g.mean_scales)) ||
           (g.mean_offsets && !aligned16(g.mean_offsets)))
         return MLC_ERR_ARG;
-      if (g.n % 8 || g.n > 16384 || (g.worker_dtype == MLC_F32 && g.global_dtype == MLC_BF16))
+      if (g.n % 8 || g.n > 24576 || (g.worker_dtype == MLC_F32 && g.global_dtype == MLC_BF16))
         return MLC_ERR_UNSUPPORTED;
     }
     if (hp->error_feedback) {

@@ -872,11 +872,11 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
                                 int64_t n, int K, const QuantForm& form, float eta_out, float mu,
                                 int nesterov, int write_back, int requant, uint8_t* mean_codes,
                                 float* mean_scales, float* mean_offsets, hipStream_t stream) {
-  if (n % 8 || n > 16384 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
+  if (n % 8 || n > 24576 || (worker_dtype == MLC_F32 && global_dtype == MLC_BF16))
     return MLC_ERR_UNSUPPORTED;
   const int g = n <= 2048 ? 64 : OT_THREADS;
   const int need = (int)((n + g * 8 - 1) / (g * 8));
-  const int nv = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
+  const int nv = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : need <= 8 ? 8 : 12;
   const long rpb = OT_THREADS / g;
   const long nblk = (rows + rpb - 1) / rpb;
   if (nblk > 0x7fffffffL) return MLC_ERR_SHAPE;
@@ -897,7 +897,7 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
     if (g == 64) { if (nv == 1) MLC_QO(WT, GT, 1, 64); else if (nv == 2) MLC_QO(WT, GT, 2, 64);   \
                    else MLC_QO(WT, GT, 4, 64); }                                                  \
     else { if (nv <= 2) MLC_QO(WT, GT, 2, 256); else if (nv == 4) MLC_QO(WT, GT, 4, 256);         \
-           else MLC_QO(WT, GT, 8, 256); }                                                         \
+           else if (nv == 8) MLC_QO(WT, GT, 8, 256); else MLC_QO(WT, GT, 12, 256); }              \
   } while (0)
   if (worker_dtype == MLC_BF16 && global_dtype == MLC_F32) MLC_QO_NV(bf16_t, float);
   else if (worker_dtype == MLC_BF16) MLC_QO_NV(bf16_t, bf16_t);

@@ -146,7 +146,7 @@ def test_outer_step_argument_errors():
     # the second quantisation needs a compressor and rows the one-pass kernel can hold
     assert call(group(), second_quantisation=1) == -5
     assert call(group(), second_quantisation=2, quant_bits=4) == -5
-    assert call(group(n=20480), second_quantisation=1, quant_bits=4) == -7
+    assert call(group(n=24584), second_quantisation=1, quant_bits=4) == -7
     assert call(group(n=12), second_quantisation=1, quant_bits=4) == -7
     # other forms of the quantiser need a compressor; the offset form needs the offsets
     assert call(group(), quant_offset=1) == -5

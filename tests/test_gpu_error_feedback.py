@@ -152,7 +152,9 @@ SQ_CASES = [
     (2, 64, 128, 3, torch.bfloat16, torch.float32, 4, False),
     (1, 50, 1000, 4, torch.bfloat16, torch.float32, 4, True),
     (1, 12, 5120, 2, torch.bfloat16, torch.bfloat16, 4, False),
-    (1, 6, 16384, 2, torch.bfloat16, torch.float32, 8, False),        # longest supported row
+    (1, 6, 16384, 2, torch.bfloat16, torch.float32, 8, False),
+    (1, 5, 20480, 2, torch.bfloat16, torch.float32, 4, True),         # 15B-scale row length
+    (1, 3, 24576, 1, torch.bfloat16, torch.float32, 4, False),        # longest supported row
     (1, 24, 768, 8, torch.bfloat16, torch.float32, 2, True),
     (1, 9, 2048, 1, torch.float32, torch.float32, 4, False),          # K = 1: second stage is the identity
 ]
