@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmuloco.so")
 MICROBENCH_PATH = os.path.join(HERE, "mlc_microbench")
-SOURCES = ["api.hip", "ns_gemm.hip", "inner_elementwise.hip", "outer.hip"]
+SOURCES = ["api.hip", "ns_gemm.hip", "ns_chain_small.hip", "inner_elementwise.hip", "outer.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,5 +1,6 @@
 // C-ABI entry points, host-side argument validation, launch planning and the optional
 // timing recorder.  Nothing here allocates device memory or synchronises the stream.
+#include <atomic>
 #include <cmath>
 #include <mutex>
 #include <vector>
@@ -13,7 +14,7 @@ namespace {
 struct TimingRecord { int family; hipEvent_t start, stop; double flops, bytes; };
 struct TimingState {
   std::mutex mu;
-  bool enabled = false;
+  std::atomic<bool> enabled{false};   // read on every launch without taking the lock
   std::vector<TimingRecord> records;
   std::vector<hipEvent_t> pool;
 };
@@ -30,11 +31,15 @@ hipEvent_t get_event(TimingState& t) {
 
 LaunchScope::LaunchScope(int family, hipStream_t s, double flops, double bytes) : slot(-1), stream(s) {
   TimingState& t = timing();
-  if (!t.enabled) return;
+  if (!t.enabled.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lock(t.mu);
   if (t.records.size() >= kMaxRecords) return;
   TimingRecord r{family, get_event(t), get_event(t), flops, bytes};
-  if (!r.start || !r.stop) return;
+  if (!r.start || !r.stop) {          // keep whichever of the two was created
+    if (r.start) t.pool.push_back(r.start);
+    if (r.stop) t.pool.push_back(r.stop);
+    return;
+  }
   (void)hipEventRecord(r.start, stream);
   t.records.push_back(r);
   slot = (int)t.records.size() - 1;
@@ -130,6 +135,12 @@ int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, 
                  float c, hipStream_t stream, int* result_buf) {
   const bool wide = p.mp <= p.np;
   const int64_t xs = p.mp * p.ldx, ss = p.sp * p.lds;
+  if (iters >= 1 && ns_chain_small_fits(p.mp, p.np)) {
+    // small matrices: all iterations in one launch, X and A resident in LDS
+    *result_buf = 1;
+    return launch_ns_chain_small(w.X[0], w.X[1], p.ldx, xs, p.mp, p.np, w.scale, chunk, iters, a, b, c,
+                                 stream);
+  }
   int cur = 0;
   for (int it = 0; it < iters; ++it) {
     const bf16_t* X = w.X[cur];

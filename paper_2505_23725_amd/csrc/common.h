@@ -49,6 +49,15 @@ __device__ __forceinline__ float wave_min(float v) {
 
 static inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
 
+// Per-device host-side caches (kernel attributes, unit counts) are arrays of this many slots.
+constexpr int MAX_DEVICES = 64;
+// Index of the current device in such a cache, or -1 when it has no slot.
+static inline int device_slot() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return -1;
+  return dev;
+}
+
 // ---- timing recorder -------------------------------------------------------------
 struct LaunchScope {
   LaunchScope(int family, hipStream_t stream, double flops, double bytes);
@@ -76,6 +85,15 @@ struct GemmDesc {
                          // tiles and store each off-diagonal tile twice
 };
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
+
+// ---- whole Newton-Schulz chain of a small matrix in one workgroup (ns_chain_small.hip) ----
+// Fits when the padded short side is 128 and the padded long side at most 512.
+bool ns_chain_small_fits(int64_t mp, int64_t np);
+// in/out: [count] padded mp x np bf16 matrices, row pitch ld, batch stride `stride`
+// (elements); scale: per matrix 1 / (norm + eps); iters >= 1.  in == out is allowed.
+int launch_ns_chain_small(const bf16_t* in, bf16_t* out, int64_t ld, int64_t stride, int64_t mp,
+                          int64_t np, const float* scale, int64_t count, int iters, float a, float b,
+                          float c, hipStream_t stream);
 
 // ---- elementwise kernels of the inner step (inner_elementwise.hip) ----------------
 int launch_momentum(const void* grad, int grad_dtype, float* mom, bf16_t* U, float* partials,

@@ -26,6 +26,7 @@
 // values a lane needs are adjacent in memory.  K-contiguous operands use the same
 // interleaved ownership so that a lane's TN output columns are adjacent and are stored
 // as one 4- or 8-byte word.
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -583,15 +584,19 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   }
 }
 
-int cus_per_xcd() {
-  static int cached = 0;
-  if (cached == 0) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || cus < NUM_XCD)
-      cus = 256;
-    cached = cus / NUM_XCD;
+// Compute units behind one L2 (one XCD) of the current device.
+int cus_per_xcd(int slot) {
+  static std::atomic<int> cached[MAX_DEVICES];
+  if (slot >= 0) {
+    const int c = cached[slot].load(std::memory_order_relaxed);
+    if (c > 0) return c;
   }
-  return cached;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < NUM_XCD)
+    cus = 256;
+  if (slot >= 0) cached[slot].store(cus / NUM_XCD, std::memory_order_relaxed);
+  return cus / NUM_XCD;
 }
 
 template <int BM, int BN, bool AKS, bool BKS>
@@ -614,20 +619,23 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   if (total <= 0 || total > (1L << 30)) return MLC_ERR_SHAPE;
   g.total_tiles = (int)total;
   g.tiles_per_xcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
-  // one workgroup per CU for the 256 x 256 tile (128 KiB of LDS each), two for 128 x 128
+  // one workgroup per CU for the 256 x 256 tile (its ring fills the 160 KiB of LDS), two for 128 x 128
   const int per_cu = (BM == 256) ? 1 : 2;
-  g.wg_per_xcd = cus_per_xcd() * per_cu;
+  const int slot = device_slot();
+  g.wg_per_xcd = cus_per_xcd(slot) * per_cu;
   if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
   g.alpha = d.alpha; g.beta = d.beta; g.gamma = d.gamma;
   g.bscale = d.bscale; g.bscale_pow = d.bscale_pow;
   const size_t lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
   auto kern = ns_gemm_bf16_kernel<BM, BN, AKS, BKS>;
-  static bool attr_set = false;   // per instantiation; raising the LDS limit is idempotent
-  if (!attr_set) {
+  // The LDS limit of a kernel is raised once per instantiation and device (the call is
+  // idempotent, so a race between two host threads only repeats it).
+  static std::atomic<bool> attr_set[MAX_DEVICES];
+  if (slot < 0 || !attr_set[slot].load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return MLC_ERR_LAUNCH;
-    attr_set = true;
+    if (slot >= 0) attr_set[slot].store(true, std::memory_order_release);
   }
   const double flops = 2.0 * BM * BN * (double)d.K * (double)total;   // executed, not nominal
   LaunchScope scope(MLC_KERNEL_NS_GEMM, stream, flops, 0.0);

@@ -1,5 +1,6 @@
 """The public header is plain C: it must compile with a C compiler, and a C program that
 names every entry point must link against the built library (nothing is executed)."""
+import ctypes as C
 import os
 import shutil
 import subprocess
@@ -48,3 +49,62 @@ def test_header_is_plain_c_and_every_entry_point_links():
                src, "-o", exe, lib, "-Wl,-rpath," + os.path.dirname(lib), "-Wl,--allow-shlib-undefined"]
         res = subprocess.run(cmd, capture_output=True, text=True)
         assert res.returncode == 0, res.stderr
+
+
+# ---- the binding's structures against the header's ------------------------------------------
+STRUCTS = {
+    "mlc_inner_group": "_InnerGroup",
+    "mlc_muon_hparams": "_MuonHParams",
+    "mlc_outer_group": "_OuterGroup",
+    "mlc_outer_hparams": "_OuterHParams",
+    "mlc_adamw_group": "_AdamWGroup",
+    "mlc_adamw_hparams": "_AdamWHParams",
+    "mlc_kernel_timing": "_KernelTiming",
+}
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="no C compiler")
+def test_binding_structures_match_the_header_field_by_field():
+    """The ctypes structures restate the header by hand.  A C program built from the header
+    prints size and offset of every field under the binding's field names (so a renamed,
+    missing or reordered field fails to compile or to match), plus the constants the
+    binding repeats."""
+    from paper_2505_23725_amd import binding
+    lines = ["#include <stddef.h>", "#include <stdio.h>", '#include "muloco.h"', "int main(void) {"]
+    for cname, pyname in STRUCTS.items():
+        st = getattr(binding, pyname)
+        lines.append(f'  printf("{cname} size %zu\\n", sizeof({cname}));')
+        for fname, _ in st._fields_:
+            lines.append(f'  printf("{cname} {fname} %zu %zu\\n", offsetof({cname}, {fname}), '
+                         f'sizeof((({cname}*)0)->{fname}));')
+    lines.append('  printf("const MLC_MAX_WORKERS %d\\nconst MLC_KERNEL_FAMILIES %d\\nconst MLC_F32 %d\\n'
+                 'const MLC_BF16 %d\\n", MLC_MAX_WORKERS, (int)MLC_KERNEL_FAMILIES, (int)MLC_F32, (int)MLC_BF16);')
+    lines += ["  return 0;", "}"]
+    with tempfile.TemporaryDirectory() as tmp:
+        src = os.path.join(tmp, "layout.c")
+        with open(src, "w") as f:
+            f.write("\n".join(lines))
+        exe = os.path.join(tmp, "layout")
+        res = subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), src, "-o", exe],
+                             capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr
+        out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split("\n")
+    seen = set()
+    for line in filter(None, out):
+        parts = line.split()
+        if parts[0] == "const":
+            expected = {"MLC_MAX_WORKERS": binding.MLC_MAX_WORKERS,
+                        "MLC_KERNEL_FAMILIES": len(binding.KERNEL_FAMILIES),
+                        "MLC_F32": binding.MLC_F32, "MLC_BF16": binding.MLC_BF16}[parts[1]]
+            assert int(parts[2]) == expected, line
+            continue
+        st = getattr(binding, STRUCTS[parts[0]])
+        if parts[1] == "size":
+            assert C.sizeof(st) == int(parts[2]), line
+            # no field of the header is missing from the binding: the fields tile the
+            # structure up to alignment padding, which the equal size and offsets imply
+            continue
+        fld = getattr(st, parts[1])
+        assert (fld.offset, fld.size) == (int(parts[2]), int(parts[3])), line
+        seen.add((parts[0], parts[1]))
+    assert len(seen) == sum(len(getattr(binding, p)._fields_) for p in STRUCTS.values())

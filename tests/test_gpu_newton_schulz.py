@@ -40,9 +40,12 @@ SHAPES = [
     (1, 128, 128),      # one tile
     (3, 128, 512),      # tiny-config wide
     (2, 512, 128),      # tiny-config tall
+    (3, 100, 380),      # ragged wide that pads to 128 x 384: one-workgroup chain, L = 384
+    (2, 128, 640),      # short side 128 but too long for the one-workgroup chain
     (2, 200, 136),      # ragged in both dimensions (pads to 256 x 256)
     (1, 72, 1000),      # ragged wide, row length not a multiple of 8? (1000 is) -> padded columns
-    (1, 333, 77),       # ragged tall, odd row length: scalar load path
+    (1, 333, 77),       # ragged tall, odd row length: scalar load path; chain held transposed
+    (300, 128, 256),    # more matrices than compute units on the one-workgroup chain
     (5, 384, 640),      # several tiles, wide
     (2, 640, 384),      # several tiles, tall
     (4, 768, 768),      # 150M-scale attention shape
