@@ -303,7 +303,9 @@ def main() -> int:
                    "step": "muon inner step + fused outer step + 4-bit quantised outer step per layer fragment"},
         "roofline": {"bound": "mfma", "achieved": ns_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ns_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "kernel": "ns_gemm_bf16_kernel",
+                     # shapes of at most 128 x 512 run the whole chain in one launch instead
+                     "kernel": ("ns_chain_small_kernel" if max(wl.d_model, wl.d_ffn) <= 512 and wl.d_model <= 128
+                                else "ns_gemm_bf16_kernel"),
                      "avg_launch_ms": gemm["total_ms"] / max(1, gemm["launches"])},
         "breakdown": breakdown,
     }
