@@ -125,21 +125,26 @@ int64_t chunk_for(const NsPlan& p, size_t ws_bytes, int64_t count) {
 }
 
 // The `iters` Newton-Schulz iterations on a chunk whose (unnormalised) input sits in X[0]
-// and whose per-matrix 1/(norm+eps) sits in `scale`.  Returns the index of the buffer that
-// holds the result; with iters == 0 the result is X[0] still unscaled.
+// and whose per-matrix partial sums of squares sit in `partials`.  Returns the index of the
+// buffer that holds the result; with iters == 0 the result is X[0] still unscaled, and its
+// factor 1/(norm+eps) sits in `scale`.
 //
 // The polynomial is folded before the last product: B' = a I + b A + c A^2, X <- B' X,
 // which is the printed iteration with one rounding to bf16 fewer.  The normalisation is
 // folded into the first iteration's scalars: A_0 = s^2 U U^T, X_1 = s B' U.
 int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
-                 float c, hipStream_t stream, int* result_buf) {
+                 float c, float eps, hipStream_t stream, int* result_buf) {
   const bool wide = p.mp <= p.np;
   const int64_t xs = p.mp * p.ldx, ss = p.sp * p.lds;
   if (iters >= 1 && ns_chain_small_fits(p.mp, p.np)) {
-    // small matrices: all iterations in one launch, X and A resident in LDS
+    // small matrices: norm and all iterations in one launch, X and A resident in LDS
     *result_buf = 1;
-    return launch_ns_chain_small(w.X[0], w.X[1], p.ldx, xs, p.mp, p.np, w.scale, chunk, iters, a, b, c,
-                                 stream);
+    return launch_ns_chain_small(w.X[0], w.X[1], p.ldx, xs, p.mp, p.np, w.partials, p.nblk, eps, chunk,
+                                 iters, a, b, c, stream);
+  }
+  {
+    const int rc = launch_norm_finalize(w.partials, p.nblk, w.scale, chunk, eps, stream);
+    if (rc != MLC_OK) return rc;
   }
   int cur = 0;
   for (int it = 0; it < iters; ++it) {
@@ -257,10 +262,8 @@ int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_
     unsigned char* dst = (unsigned char*)out + (size_t)c0 * m * n * es;
     rc = launch_ns_load(src, io_dtype, w.X[0], w.partials, p.nblk, cc, m, n, p.mp, p.np, p.ldx, stream);
     if (rc != MLC_OK) return rc;
-    rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, eps, stream);
-    if (rc != MLC_OK) return rc;
     int res = 0;
-    rc = run_ns_chunk(p, w, cc, iters, a, b, c, stream, &res);
+    rc = run_ns_chunk(p, w, cc, iters, a, b, c, eps, stream, &res);
     if (rc != MLC_OK) return rc;
     rc = launch_ns_store(w.X[res], iters == 0 ? w.scale : nullptr, dst, io_dtype, cc, m, n, p.mp,
                          p.ldx, stream);
@@ -328,10 +331,8 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
       rc = launch_momentum(grad, g.grad_dtype, mom, w.X[0], w.partials, p.nblk, cc, g.m, g.n, p.mp,
                            p.np, p.ldx, hp->beta, hp->nesterov, stream);
       if (rc != MLC_OK) return rc;
-      rc = launch_norm_finalize(w.partials, p.nblk, w.scale, cc, hp->ns_eps, stream);
-      if (rc != MLC_OK) return rc;
       int res = 0;
-      rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, stream, &res);
+      rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, hp->ns_eps, stream, &res);
       if (rc != MLC_OK) return rc;
       rc = launch_param_update(param, g.param_dtype, w.X[res], hp->ns_iters == 0 ? w.scale : nullptr,
                                cc, g.m, g.n, p.mp, p.ldx, decay_factor, hp->eta * g.lr_scale, stream);

@@ -90,10 +90,11 @@ int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
 // Fits when the padded short side is 128 and the padded long side at most 512.
 bool ns_chain_small_fits(int64_t mp, int64_t np);
 // in/out: [count] padded mp x np bf16 matrices, row pitch ld, batch stride `stride`
-// (elements); scale: per matrix 1 / (norm + eps); iters >= 1.  in == out is allowed.
+// (elements); partials: per matrix nblk partial sums of squares of the input, from which the
+// kernel forms 1 / (norm + eps); iters >= 1.  in == out is allowed.
 int launch_ns_chain_small(const bf16_t* in, bf16_t* out, int64_t ld, int64_t stride, int64_t mp,
-                          int64_t np, const float* scale, int64_t count, int iters, float a, float b,
-                          float c, hipStream_t stream);
+                          int64_t np, const float* partials, int nblk, float eps, int64_t count,
+                          int iters, float a, float b, float c, hipStream_t stream);
 
 // ---- elementwise kernels of the inner step (inner_elementwise.hip) ----------------
 int launch_momentum(const void* grad, int grad_dtype, float* mom, bf16_t* U, float* partials,

@@ -9,8 +9,9 @@
 // from the first iteration to the last; HBM is touched once to read X and once to write it.
 // The arithmetic and its rounding points are those of the batched path: A, B' and X are
 // rounded to bf16 where that path stores them, products accumulate in fp32 on
-// v_mfma_f32_32x32x16_bf16, the normalisation 1/(|U| + eps) enters as a factor s^2 of the first
-// Gram matrix and s of the first product with X.
+// v_mfma_f32_32x32x16_bf16, the normalisation s = 1/(|U| + eps) enters as a factor s^2 of the
+// first Gram matrix and s of the first product with X.  The kernel forms s itself from the
+// partial sums of squares that the pass which wrote U left per matrix.
 //
 // A tall matrix (more rows than columns) is held transposed, so that the resident X is
 // always 128 x L with L >= 128: the iteration commutes with transposition.
@@ -39,7 +40,9 @@ struct ChainArgs {
   long ld, stride;
   int tall;                // 0: matrix is 128 x L in memory ; 1: L x 128
   int L;                   // padded long side, a multiple of 128, <= LP
-  const float* scale;      // per matrix 1 / (norm + eps)
+  const float* partials;   // per matrix nblk partial sums of squares of the input
+  int nblk;
+  float eps;               // scale = 1 / (sqrt(sum) + eps)
   int iters;               // >= 1
   float a, b, c;
 };
@@ -78,7 +81,11 @@ __global__ __launch_bounds__(256) void ns_chain_small_kernel(ChainArgs g) {
   const bf16_t* in = g.in + (long)blockIdx.x * g.stride;
   bf16_t* out = g.out + (long)blockIdx.x * g.stride;
   const int L = g.L;
-  const float s = g.scale[blockIdx.x];
+  // 1 / (|U| + eps) from the partial sums the pass that wrote U left behind (every wavefront
+  // adds them up for itself, in the same order)
+  float tot = 0.f;
+  for (int i = lane; i < g.nblk; i += 64) tot += g.partials[(long)blockIdx.x * g.nblk + i];
+  const float s = 1.0f / (sqrtf(wave_sum(tot)) + g.eps);
 
   // ---- X from memory into LDS (columns L .. LP-1 are zero) -----------------------------
   if (!g.tall) {
@@ -359,11 +366,11 @@ bool ns_chain_small_fits(int64_t mp, int64_t np) {
 }
 
 int launch_ns_chain_small(const bf16_t* in, bf16_t* out, int64_t ld, int64_t stride, int64_t mp,
-                          int64_t np, const float* scale, int64_t count, int iters, float a, float b,
-                          float c, hipStream_t stream) {
+                          int64_t np, const float* partials, int nblk, float eps, int64_t count,
+                          int iters, float a, float b, float c, hipStream_t stream) {
   if (!ns_chain_small_fits(mp, np) || mp % 128 || np % 128) return MLC_ERR_SHAPE;
-  if (!in || !out || !scale) return MLC_ERR_NULL;
-  if (iters < 1 || count < 1 || count > 0x7fffffff) return MLC_ERR_ARG;
+  if (!in || !out || !partials) return MLC_ERR_NULL;
+  if (iters < 1 || count < 1 || count > 0x7fffffff || nblk < 1) return MLC_ERR_ARG;
   const bool tall = mp > np;
   // every 16-byte access stays inside a row of the padded matrix
   if (ld % 8 || stride % 8 || ld < np || stride < mp * ld) return MLC_ERR_SHAPE;
@@ -371,7 +378,8 @@ int launch_ns_chain_small(const bf16_t* in, bf16_t* out, int64_t ld, int64_t str
   g.in = in; g.out = out; g.ld = ld; g.stride = stride;
   g.tall = tall ? 1 : 0;
   g.L = (int)(tall ? mp : np);
-  g.scale = scale; g.iters = iters; g.a = a; g.b = b; g.c = c;
+  g.partials = partials; g.nblk = nblk; g.eps = eps;
+  g.iters = iters; g.a = a; g.b = b; g.c = c;
   if (g.L <= 128) return launch_tt<1>(g, count, stream);
   if (g.L <= 256) return launch_tt<2>(g, count, stream);
   return launch_tt<4>(g, count, stream);

@@ -53,6 +53,8 @@ CASES = [
     (2, 128, 128, torch.float32, torch.float32),
     (2, 128, 512, torch.float32, torch.float32),
     (2, 512, 128, torch.float32, torch.float32),
+    (3, 100, 380, torch.bfloat16, torch.float32),      # ragged, one-launch path, L = 384
+    (2, 128, 640, torch.bfloat16, torch.bfloat16),      # short side 128, too long for that path
     (3, 256, 384, torch.bfloat16, torch.bfloat16),
     (2, 200, 136, torch.bfloat16, torch.float32),
     (1, 333, 77, torch.float32, torch.bfloat16),
