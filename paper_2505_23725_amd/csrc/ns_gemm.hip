@@ -263,6 +263,20 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
     rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(g.C) + (long)tc.b * g.strideC, 0,
                                            0xffffffff, 0x00020000);
   const int diag = col0 - row_lane;     // row offset (within the lane's rows) that meets column col0
+  // C is fetched one quarter ahead: the loads of quarter q + 1 are in flight while quarter q
+  // is converted and stored, so only the first quarter waits for memory.
+  u32x2 cnext[4][TM];
+  auto load_c = [&](int q) {
+#pragma unroll
+    for (int rl = 0; rl < 4; ++rl)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const unsigned int soff = (unsigned int)(TM * (8 * q + rl) + i) * ldc2;
+        if constexpr (TN == 2) cnext[rl][i].x = __builtin_amdgcn_raw_buffer_load_b32(rc, voff_c, soff, 0);
+        else cnext[rl][i] = __builtin_amdgcn_raw_buffer_load_b64(rc, voff_c, soff, 0);
+      }
+  };
+  if constexpr (HAS_C) load_c(0);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     // keep the scheduler from pulling the next quarter's accumulator reads up here: all 256
@@ -274,11 +288,8 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
 #pragma unroll
       for (int rl = 0; rl < 4; ++rl)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const unsigned int soff = (unsigned int)(TM * (8 * q + rl) + i) * ldc2;
-          if constexpr (TN == 2) cval[rl][i].x = __builtin_amdgcn_raw_buffer_load_b32(rc, voff_c, soff, 0);
-          else cval[rl][i] = __builtin_amdgcn_raw_buffer_load_b64(rc, voff_c, soff, 0);
-        }
+        for (int i = 0; i < TM; ++i) cval[rl][i] = cnext[rl][i];
+      if (q < 3) load_c(q + 1);
     }
 #pragma unroll
     for (int rl = 0; rl < 4; ++rl) {
