@@ -64,6 +64,8 @@ QCASES = [
     (1, 9, 6, 3, torch.float32, torch.float32),           # short rows: scalar path
     (1, 40, 2560, 4, torch.bfloat16, torch.bfloat16),     # a 3.1B-scale row length
     (1, 16, 10240, 1, torch.bfloat16, torch.float32),
+    (1, 12, 10240, 4, torch.bfloat16, torch.float32),     # six vectors per thread, K = 4
+    (1, 6, 16384, 2, torch.bfloat16, torch.float32),      # eight vectors per thread
     (1, 6, 20480, 2, torch.bfloat16, torch.float32),      # 15B-scale row length
     (1, 10, 5120, 3, torch.bfloat16, torch.float32),
     (2, 9, 2048, 2, torch.float32, torch.float32),        # widest wavefront-per-row case
