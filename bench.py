@@ -185,8 +185,8 @@ def main() -> int:
         del groups
         torch.cuda.empty_cache()
 
-    # Top-k sparsified outer step (5 % kept, error feedback) over the whole model: four selection
-    # passes and the sparsified update; the figure is algorithmic bytes of all five passes.
+    # Top-k sparsified outer step (5 % kept, error feedback) over the whole model: three selection
+    # passes and the sparsified update; the figure is algorithmic bytes of all four passes.
     topk_fig = None
     if job.K * n_elems * 4 + (1 << 30) < torch.cuda.mem_get_info()[0]:
         groups = []

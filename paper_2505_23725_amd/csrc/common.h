@@ -125,7 +125,8 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
 // residual (error-feedback) accumulators per worker; all null = no error feedback
 struct ResidualPtrs { float* p[MLC_MAX_WORKERS]; };
 // Radix-select state of one (worker, matrix) pair of the top-k sparsifier.
-struct TopkState { unsigned int hist[256]; unsigned int prefix, mask, rank, pad; };
+constexpr int TOPK_BINS = 2048;     // widest digit of the radix select: 11 bits
+struct TopkState { unsigned int hist[TOPK_BINS]; unsigned int prefix, mask, rank, pad; };
 size_t topk_workspace_bytes(int64_t count, int K);
 // thresholds: per worker [count] floats (may be null): the k-th largest magnitude found.
 int launch_topk_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int global_dtype, float* u,

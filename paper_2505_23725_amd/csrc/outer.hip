@@ -553,24 +553,27 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
 // Of each matrix of each worker the k entries of largest magnitude are kept (all entries
 // that tie with the k-th one included).  The k-th largest magnitude is found exactly by a
 // radix select over the bit pattern of |v| (ordered like an unsigned for non-negative
-// floats): four passes of 8 bits, each a histogram of the entries that match the digits
-// found so far, then the digit in which the k-th entry falls.
+// floats; bit 31 is always clear): three passes with digits of 11, 10 and 10 bits, each a
+// histogram of the entries that match the digits found so far, then the digit in which the
+// k-th entry falls.
 __global__ void topk_init_kernel(TopkState* st, unsigned int kcount) {
   TopkState& s = st[blockIdx.x];
-  s.hist[threadIdx.x] = 0u;
+  for (int i = threadIdx.x; i < TOPK_BINS; i += blockDim.x) s.hist[i] = 0u;
   if (threadIdx.x == 0) { s.prefix = 0u; s.mask = 0u; s.rank = kcount; s.pad = 0u; }
 }
 
 template <typename WT, typename GT, bool VEC>
 __global__ __launch_bounds__(OT_THREADS) void topk_hist_kernel(
     WorkerPtrs w, const GT* __restrict__ theta_g, ResidualPtrs ef, TopkState* st, long elems, int count,
-    int shift, float ef_beta) {
-  __shared__ unsigned int lh[OT_THREADS / 64][256];
+    int shift, int nbins, float ef_beta) {
+  __shared__ unsigned int lh[OT_THREADS / 64][TOPK_BINS];     // one histogram per wavefront
   const long b = blockIdx.y;
   const int k = blockIdx.z;
   TopkState& s = st[(long)k * count + b];
   const unsigned int prefix = s.prefix, mask = s.mask;
-  for (int i = threadIdx.x; i < (OT_THREADS / 64) * 256; i += OT_THREADS) (&lh[0][0])[i] = 0u;
+  const unsigned int digit_mask = (unsigned int)nbins - 1u;
+  for (int wv = 0; wv < OT_THREADS / 64; ++wv)
+    for (int i = threadIdx.x; i < nbins; i += OT_THREADS) lh[wv][i] = 0u;
   __syncthreads();
   unsigned int* mine = lh[threadIdx.x >> 6];
   const GT* tg = theta_g + b * elems;
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(OT_THREADS) void topk_hist_kernel(
       const float v = res ? ef_input(d, e[j], ef_beta) : d;
       const unsigned int key = __float_as_uint(fabsf(v));
       if ((key & mask) == prefix) {
-        const unsigned int bin = (key >> shift) & 255u;
+        const unsigned int bin = (key >> shift) & digit_mask;
         if (bin == cur) {
           ++run;
         } else {
@@ -606,30 +609,64 @@ __global__ __launch_bounds__(OT_THREADS) void topk_hist_kernel(
   }
   if (run) atomicAdd(&mine[cur], run);
   __syncthreads();
-  unsigned int tot = 0u;
+  for (int i = threadIdx.x; i < nbins; i += OT_THREADS) {
+    unsigned int tot = 0u;
 #pragma unroll
-  for (int wv = 0; wv < OT_THREADS / 64; ++wv) tot += lh[wv][threadIdx.x];
-  if (tot) atomicAdd(&s.hist[threadIdx.x], tot);
+    for (int wv = 0; wv < OT_THREADS / 64; ++wv) tot += lh[wv][i];
+    if (tot) atomicAdd(&s.hist[i], tot);
+  }
 }
 
-// The digit that holds the k-th largest entry: scan the histogram from the top.
-__global__ void topk_pick_kernel(TopkState* st, int shift) {
+// The digit that holds the k-th largest entry: the highest bin b for which the bins b and
+// above hold at least `rank` entries (bin 0 if none does).  Thread t owns the PER = nbins / 256
+// adjacent bins [PER t, PER (t + 1)); a suffix scan over the per-thread sums finds the owner.
+__global__ __launch_bounds__(256) void topk_pick_kernel(TopkState* st, int shift, int nbins) {
   TopkState& s = st[blockIdx.x];
-  __shared__ unsigned int h[256];
-  h[threadIdx.x] = s.hist[threadIdx.x];
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned int above = 0u, rank = s.rank;
-    int bin = 255;
-    for (; bin > 0; --bin) {
-      if (above + h[bin] >= rank) break;
-      above += h[bin];
-    }
-    s.prefix |= (unsigned int)bin << shift;
-    s.mask |= 255u << shift;
-    s.rank = rank - above;
+  __shared__ unsigned int suffix[256];       // entries in the bins of threads t .. 255
+  const int t = threadIdx.x;
+  const int per = nbins / 256;               // 8 or 4
+  constexpr int MAX_PER = TOPK_BINS / 256;
+  unsigned int h[MAX_PER];
+  unsigned int mine = 0u;
+#pragma unroll
+  for (int i = 0; i < MAX_PER; ++i) {
+    h[i] = i < per ? s.hist[t * per + i] : 0u;
+    mine += h[i];
   }
-  s.hist[threadIdx.x] = 0u;        // ready for the next pass
+  suffix[t] = mine;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    const unsigned int add = t + off < 256 ? suffix[t + off] : 0u;
+    __syncthreads();
+    suffix[t] += add;
+    __syncthreads();
+  }
+  const unsigned int rank = s.rank;
+  const unsigned int above = suffix[t] - mine;          // entries in the bins of threads t+1 .. 255
+  const unsigned int total = suffix[0];
+  __syncthreads();                                       // everyone has read the old rank
+#pragma unroll
+  for (int i = 0; i < MAX_PER; ++i)
+    if (i < per) s.hist[t * per + i] = 0u;               // ready for the next pass
+  const bool owner = (above < rank && above + mine >= rank) || (t == 0 && total < rank);
+  if (owner) {
+    // from the thread's top bin down (bins at and beyond `per` are empty); with
+    // total < rank (more entries asked for than matched) this ends in bin 0 of thread 0
+    unsigned int ab = above;
+    int pick = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = MAX_PER - 1; i > 0; --i) {
+      if (!found) {
+        if (ab + h[i] >= rank) { pick = i; found = true; }
+        else ab += h[i];
+      }
+    }
+    const unsigned int bin = (unsigned int)(t * per + pick);
+    s.prefix |= bin << shift;
+    s.mask |= ((unsigned int)nbins - 1u) << shift;
+    s.rank = rank - ab;
+  }
 }
 
 template <typename WT, typename GT, bool VEC>
@@ -928,23 +965,26 @@ int launch_topk_outer(const WorkerPtrs& w, int worker_dtype, void* theta_g, int 
   const double last_bytes = (double)count * elems * (K * esize(worker_dtype) * (write_back ? 2 : 1) +
                                                      (has_residuals(ef) ? 8.0 * K : 0.0) +
                                                      2 * esize(global_dtype) + 8);
-  LaunchScope scope(MLC_KERNEL_TOPK, stream, 0.0, 4 * pass_bytes + last_bytes);
+  LaunchScope scope(MLC_KERNEL_TOPK, stream, 0.0, 3 * pass_bytes + last_bytes);
   hipLaunchKernelGGL(topk_init_kernel, dim3(n_states), dim3(256), 0, stream, st, kcount);
-  for (int shift = 24; shift >= 0; shift -= 8) {
+  // digits of 11, 10 and 10 bits cover bits 30 .. 0 of |v|
+  const int shifts[3] = {20, 10, 0}, bins[3] = {2048, 1024, 1024};
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = shifts[pass], nbins = bins[pass];
 #define MLC_CALL(WT, GT)                                                                          \
   do {                                                                                            \
     if (vec)                                                                                      \
       hipLaunchKernelGGL((topk_hist_kernel<WT, GT, true>), dim3(nblk, (unsigned)count, K),         \
                          dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, ef, st, elems,       \
-                         (int)count, shift, ef_beta);                                             \
+                         (int)count, shift, nbins, ef_beta);                                      \
     else                                                                                          \
       hipLaunchKernelGGL((topk_hist_kernel<WT, GT, false>), dim3(nblk, (unsigned)count, K),        \
                          dim3(OT_THREADS), 0, stream, w, (const GT*)theta_g, ef, st, elems,       \
-                         (int)count, shift, ef_beta);                                             \
+                         (int)count, shift, nbins, ef_beta);                                      \
   } while (0)
     MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
 #undef MLC_CALL
-    hipLaunchKernelGGL(topk_pick_kernel, dim3(n_states), dim3(256), 0, stream, st, shift);
+    hipLaunchKernelGGL(topk_pick_kernel, dim3(n_states), dim3(256), 0, stream, st, shift, nbins);
   }
   const float inv_k = 1.0f / (float)K;
 #define MLC_CALL(WT, GT)                                                                          \

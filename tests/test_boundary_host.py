@@ -216,5 +216,5 @@ def test_topk_argument_errors():
     assert call(error_feedback=1, ef_beta=1.0) == -1      # residuals NULL
     assert call(g=dict(global_param=None)) == -1
     arr = (B._OuterGroup * 1)(B._OuterGroup(count=3, m=4, n=16))
-    assert lib.muloco_topk_workspace_bytes(arr, 1, K) == 3 * K * 260 * 4
+    assert lib.muloco_topk_workspace_bytes(arr, 1, K) == 3 * K * (2048 + 4) * 4
     assert lib.muloco_topk_workspace_bytes(arr, 1, 0) == 0

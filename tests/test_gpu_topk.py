@@ -45,7 +45,7 @@ def test_topk_outer_step_matches_oracle(cnt, m, n, K, wd, gd, frac, ef):
     grp = mlc.OuterGroup(ws, tg, u, None, taus, res)
     hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, error_feedback=ef, ef_beta=0.9)
     need = mlc.muloco_topk_workspace_bytes([grp], K)
-    assert need == cnt * K * 260 * 4
+    assert need == cnt * K * (2048 + 4) * 4     # a 2048-bin histogram and 4 words per (worker, matrix)
     wsp = torch.full((need,), 0xCD, dtype=torch.uint8, device=DEV)          # contents must not matter
     mlc.muloco_topk_outer_step([grp], hp, frac, wsp)
     torch.cuda.synchronize()
@@ -69,7 +69,8 @@ def test_topk_second_call_reuses_the_workspace():
     cnt, m, n, K = 2, 64, 128, 2
     tg0, ws0, u0 = _inputs(cnt, m, n, K, torch.bfloat16, torch.float32, 5)
     hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, write_back=False)
-    wsp = torch.empty((cnt * K * 260 * 4,), dtype=torch.uint8, device=DEV)
+    grp0 = mlc.OuterGroup([w.to(DEV) for w in ws0], tg0.to(DEV), u0.to(DEV))
+    wsp = torch.empty((mlc.muloco_topk_workspace_bytes([grp0], K),), dtype=torch.uint8, device=DEV)
     outs = []
     for _ in range(2):
         tg, u = tg0.to(DEV), u0.to(DEV)
