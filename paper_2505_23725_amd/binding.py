@@ -140,6 +140,9 @@ def _dev_ptr(t: torch.Tensor, what: str) -> int:
         raise ValueError(f"{what} must live on the GPU")
     if not t.is_contiguous():
         raise ValueError(f"{what} must be contiguous")
+    if t.device.index != torch.cuda.current_device():
+        # kernels are launched on the current device's stream; the library does no peer access
+        raise ValueError(f"{what} lives on {t.device}, the current device is cuda:{torch.cuda.current_device()}")
     return t.data_ptr()
 
 
