@@ -69,7 +69,7 @@ const char* muloco_strerror(int code);
  * workspace   at least newton_schulz_workspace_bytes(count, m, n) bytes, 256-byte
  *             aligned.  A smaller work space that still holds one matrix is accepted;
  *             the batch is then processed in several chunks.
- * An all-zero matrix gives an all-zero result.
+ * An all-zero matrix gives an all-zero result (for every eps >= 0).
  */
 size_t newton_schulz_workspace_bytes(int64_t count, int64_t m, int64_t n);
 /* Smallest accepted work space (one matrix per chunk). */
@@ -142,8 +142,8 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups,
  *     dequantised value = (float)q * scale
  * n must be a multiple of 8 / bits.
  *
- * Offset form (quant_offset = 1; the paper's wording: levels over a fixed range, an offset
- * and a number of levels): the range is [lo, hi] = [min, max] of the values, L = 2^bits - 1,
+ * Offset form (quant_offset = 1; the linear quantiser of paper Sec. 2 "Compressed
+ * Communication" in its general shape): the range is [lo, hi] = [min, max] of the values, L = 2^bits - 1,
  *     scale = fl32(hi - lo) / L;  q = clamp(rint(fl32(delta - lo) / scale), 0, L), 0 if scale = 0
  *     code = q;  dequantised value = fl32(fl32((float)q * scale) + lo);  lo goes to offsets.
  * Scope (quant_per_matrix = 1; the paper's global variant): one range per matrix instead of

@@ -236,17 +236,23 @@ def dequantize_rowwise(q, scale):
     return (np.asarray(q, np.float32) * np.asarray(scale, np.float32)[:, None]).astype(np.float32)
 
 
+def mean_fp32(sent):
+    """fp32 mean of the workers' dequantised values, summed in worker order and multiplied by
+    fl32(1 / K): Psi = fl32(((s_1 + s_2) + ... + s_K) * fl32(1 / K))."""
+    K = len(sent)
+    acc = np.asarray(sent[0]).astype(np.float32)
+    for s in sent[1:]:
+        acc = (acc + np.asarray(s).astype(np.float32)).astype(np.float32)
+    inv_k = np.float32(1.0) / np.float32(K)
+    return (acc * inv_k).astype(np.float32)
+
+
 def requantize_mean(sent_f32, bits=4):
     """The dequantise-reduce-quantise step between the two collectives: fp32 mean of the
     workers' dequantised values in worker order, quantised row-wise again.
 
     Returns (q', scale', psi float32 before the second quantisation)."""
-    K = len(sent_f32)
-    acc = np.asarray(sent_f32[0], dtype=np.float32).copy()
-    for s in sent_f32[1:]:
-        acc = (acc + np.asarray(s, dtype=np.float32)).astype(np.float32)
-    inv_k = np.float32(1.0) / np.float32(K)
-    psi = (acc * inv_k).astype(np.float32)
+    psi = mean_fp32(sent_f32)
     q, scale = quantize_values_rowwise(psi, bits)
     return q, scale, psi
 
@@ -306,11 +312,7 @@ def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bit
             deltas.append(pseudogradient(theta_g, th))
     if second_quantisation:
         assert quant_bits, "the second quantisation needs a compressor"
-        K = len(deltas)
-        acc = deltas[0].astype(np.float32)
-        for d in deltas[1:]:
-            acc = (acc + d.astype(np.float32)).astype(np.float32)
-        psi32 = (acc * (np.float32(1.0) / np.float32(K))).astype(np.float32)
+        psi32 = mean_fp32(deltas)     # the stage requantize_mean pins by hand
         q2, s2, lo2 = quantize_values(psi32, quant_bits, **form)
         out["mean_q"], out["mean_scales"], out["mean_offsets"] = (
             q2.astype(np.int8) if not quant_offset else q2), s2, lo2

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(EW_THREADS) void muon_momentum_kernel(
   if (threadIdx.x == 0) partials[(long)b * gridDim.x + blockIdx.x] = tot;
 }
 
-// scale[b] = 1 / (sqrt(sum_b) + eps)
+// scale[b] = 1 / (sqrt(sum_b) + eps); an all-zero matrix gets 0, also when eps = 0
 __global__ __launch_bounds__(EW_THREADS) void muon_norm_kernel(const float* __restrict__ partials,
                                                                int nblk, float* __restrict__ scale,
                                                                float eps) {
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(EW_THREADS) void muon_norm_kernel(const float* __re
   float s = 0.f;
   for (int i = threadIdx.x; i < nblk; i += EW_THREADS) s += partials[(long)b * nblk + i];
   const float tot = block_sum(s);
-  if (threadIdx.x == 0) scale[b] = 1.0f / (sqrtf(tot) + eps);
+  if (threadIdx.x == 0) scale[b] = tot > 0.f ? 1.0f / (sqrtf(tot) + eps) : 0.f;
 }
 
 // W <- decay_factor * W - step * oscale_b * O     (decay_factor = 1 - eta*lambda,

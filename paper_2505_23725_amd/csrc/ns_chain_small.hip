@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void ns_chain_small_kernel(ChainArgs g) {
   // adds them up for itself, in the same order)
   float tot = 0.f;
   for (int i = lane; i < g.nblk; i += 64) tot += g.partials[(long)blockIdx.x * g.nblk + i];
-  const float s = 1.0f / (sqrtf(wave_sum(tot)) + g.eps);
+  const float sumsq = wave_sum(tot);
+  const float s = sumsq > 0.f ? 1.0f / (sqrtf(sumsq) + g.eps) : 0.f;   // all-zero matrix: 0, also when eps = 0
 
   // ---- X from memory into LDS (columns L .. LP-1 are zero) -----------------------------
   if (!g.tall) {

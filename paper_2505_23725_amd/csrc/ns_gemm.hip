@@ -92,7 +92,7 @@ __device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, 
   asm volatile("s_mov_b32 m0, %0\n\t"
                "s_nop 0\n\t"
                "buffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+               :: "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {

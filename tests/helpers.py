@@ -8,7 +8,10 @@ Comparison rules (derived from the arithmetic):
   The rms floor is there because these outputs are sums of terms of the tensor's typical
   magnitude (theta - mu u - eta Psi): the fp32 rounding error of such a sum scales with its
   operands, not with a result that cancellation happened to make small.
-* Newton-Schulz outputs (bf16 matrix-core path): relative Frobenius error <= 2e-2 per matrix.
+* Newton-Schulz outputs (bf16 matrix-core path): relative Frobenius error <= 2e-2 per matrix,
+  and so that a wrong block cannot hide in the norm of a large matrix: the same ratio on
+  every 256 x 256 block of the output (<= 3e-2: a block averages over fewer elements), and
+  the largest element error <= 10 x the rms error and <= a quarter of the largest element.
 * quantiser codes and scales: exact equality.
 """
 import numpy as np
@@ -36,6 +39,44 @@ def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
     den = np.linalg.norm(ref.ravel())
     num = np.linalg.norm((got - ref).ravel())
     return float(num / den) if den > 0 else float(num)
+
+
+NS_TILE = 256          # block edge of the per-block check (the GEMM's output tile)
+NS_TILE_TOL = 3e-2
+NS_MAX_OVER_RMS = 10.0
+NS_MAX_FRACTION = 0.25
+
+
+def ns_error_stats(got: np.ndarray, ref: np.ndarray) -> dict:
+    """Error figures of one Newton-Schulz output against the oracle's."""
+    d = got - ref
+    m, n = ref.shape
+    worst_tile, where = 0.0, (0, 0)
+    for i in range(0, m, NS_TILE):
+        for j in range(0, n, NS_TILE):
+            den = np.linalg.norm(ref[i:i + NS_TILE, j:j + NS_TILE])
+            num = np.linalg.norm(d[i:i + NS_TILE, j:j + NS_TILE])
+            r = float(num / den) if den > 0 else float(num)
+            if r > worst_tile:
+                worst_tile, where = r, (i, j)
+    rms = float(np.sqrt(np.mean(d * d)))
+    return {"fro": rel_fro(got, ref), "tile": worst_tile, "tile_at": where,
+            "max": float(np.max(np.abs(d))), "rms": rms, "ref_max": float(np.max(np.abs(ref)))}
+
+
+def assert_ns_close(got: np.ndarray, ref: np.ndarray, what: str, tol: float = NS_TOL) -> dict:
+    """All comparison rules of a Newton-Schulz output; `tol` scales every bound alike."""
+    st = ns_error_stats(got, ref)
+    k = tol / NS_TOL
+    assert st["fro"] <= tol, f"{what}: relative Frobenius error {st['fro']:.3e} > {tol:.1e}"
+    assert st["tile"] <= NS_TILE_TOL * k, (f"{what}: block at {st['tile_at']} has relative Frobenius "
+                                           f"error {st['tile']:.3e} > {NS_TILE_TOL * k:.1e}")
+    if st["rms"] > 0:
+        assert st["max"] <= NS_MAX_OVER_RMS * st["rms"], (
+            f"{what}: largest element error {st['max']:.3e} is {st['max'] / st['rms']:.1f}x the rms error")
+    assert st["max"] <= NS_MAX_FRACTION * k * st["ref_max"] + 1e-30, (
+        f"{what}: largest element error {st['max']:.3e} vs largest element {st['ref_max']:.3e}")
+    return st
 
 
 def assert_fp32_close(got_t: torch.Tensor, ref: np.ndarray, what: str, tol: float = EW_TOL):
@@ -70,3 +111,23 @@ def update_error_bf16(W_gpu_t: torch.Tensor, W0: np.ndarray, W_ref: np.ndarray) 
     ulp = storage.bf16_ulp(W_ref)
     excess = float(np.sum(d * d) - np.sum(ulp * ulp) / 12.0)
     return float(np.sqrt(max(excess, 0.0)) / np.linalg.norm(W_ref - W0))
+
+
+UPDATE_ELEMENT_C = 0.05
+
+
+def assert_update_elements(W_gpu_t: torch.Tensor, W_ref: np.ndarray, O_ref: np.ndarray, step: float,
+                           what: str) -> float:
+    """Element-wise bound on the parameters after an inner step, so that a wrong block cannot
+    hide in the Frobenius norm of the update: every element must be a storage rounding of a
+    value whose orthogonalised term is off by at most UPDATE_ELEMENT_C * max|O| (the element
+    bound of the Newton-Schulz output: 10 x its rms error of 1e-2, with rms(O) about a fifth
+    of max|O|, plus margin).  step = eta * lr_scale.  Returns the worst ratio to the bound."""
+    got = to_f64(W_gpu_t)
+    half_ulp = storage.bf16_ulp(W_ref) * (0.5 + 2.0 ** -12) if W_gpu_t.dtype == torch.bfloat16 else 0.0
+    bound = half_ulp + UPDATE_ELEMENT_C * abs(step) * float(np.max(np.abs(O_ref))) + 1e-6 * np.abs(W_ref)
+    ratio = np.abs(got - W_ref) / bound
+    worst = float(ratio.max())
+    assert worst <= 1.0, (f"{what}: {int((ratio > 1).sum())} of {ratio.size} elements off by more than the "
+                          f"element bound, worst {worst:.2f}x")
+    return worst

@@ -7,7 +7,7 @@ import torch
 import paper_2505_23725_amd as mlc
 import synth_inputs as S
 from oracle import muon
-from helpers import NS_TOL, rel_fro, to_f64
+from helpers import NS_TOL, assert_ns_close, to_f64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -30,9 +30,8 @@ def _check(x_cpu, out_cpu, iters=5, coeffs=muon.NS_COEFFS, tol=NS_TOL):
     worst = 0.0
     for i in range(xs.shape[0]):
         ref = muon.newton_schulz(to_f64(xs[i]), iters, coeffs)
-        err = rel_fro(to_f64(os_[i]), ref)
-        worst = max(worst, err)
-        assert err <= tol, f"matrix {i} of shape {tuple(xs[i].shape)}: rel. Frobenius error {err:.3e}"
+        st = assert_ns_close(to_f64(os_[i]), ref, f"matrix {i} of shape {tuple(xs[i].shape)}", tol)
+        worst = max(worst, st["fro"])
     return worst
 
 
@@ -93,6 +92,24 @@ def test_zero_matrix_and_determinism():
     assert torch.count_nonzero(a[1]) == 0
     assert torch.isfinite(a.float()).all()
     _check(x, a)
+
+
+def test_zero_matrix_with_eps_zero_stays_zero():
+    # 1 / (norm + eps) must not turn into inf * 0 when both the matrix and eps are zero
+    for shape in [(2, 128, 256), (2, 256, 384)]:      # one-workgroup chain, batched products
+        x = S.normal(shape, S.GRAD_STD, seed=6, stream=shape[2], dtype=torch.bfloat16)
+        x[0].zero_()
+        xd = x.to(DEV)
+        out = torch.empty_like(xd)
+        ws = torch.empty(mlc.newton_schulz_workspace_bytes(*shape), dtype=torch.uint8, device=DEV)
+        for iters in (0, 5):
+            mlc.newton_schulz(xd, out, ws, iters=iters, eps=0.0)
+            torch.cuda.synchronize()
+            o = out.cpu()
+            assert torch.count_nonzero(o[0]) == 0
+            assert torch.isfinite(o.float()).all()
+            ref = muon.newton_schulz(to_f64(x[1]), iters, eps=0.0)
+            assert_ns_close(to_f64(o[1]), ref, f"{shape} eps=0 iters={iters}", 4e-3 if iters == 0 else NS_TOL)
 
 
 def test_singular_values_land_in_the_band():

@@ -44,13 +44,14 @@ def test_tiny_workload_h8_then_outer_step():
             err = rel_fro(to_f64(W_gpu[gi][i]) - th0[i], W[i] - th0[i])
             worst = max(worst, err)
             assert err <= NS_TOL, f"group {gi} matrix {i}: displacement error {err:.3e}"
-        # outer step: oracle on its own trajectory
-        out = diloco.outer_step(th0.reshape(-1, n), np.zeros((cnt * m, n)), [W.reshape(-1, n)],
+        # outer step: the oracle starts from the parameters the GPU reached after its H inner
+        # steps, so this leg is an elementwise fp32 path and is held to its own tolerance
+        out = diloco.outer_step(th0.reshape(-1, n), np.zeros((cnt * m, n)), [to_f64(W_gpu[gi]).reshape(-1, n)],
                                 eta_out=wl.eta_out, mu=wl.mu)
-        u_gpu = to_f64(job.u[gi].cpu()).reshape(-1, n)
+        assert_fp32_close(job.u[gi].cpu().reshape(-1, n), out["u"], f"group {gi}: outer momentum")
+        assert_fp32_close(job.theta_g[gi].cpu().reshape(-1, n), out["theta"], f"group {gi}: theta_g")
         th_gpu = to_f64(job.theta_g[gi].cpu()).reshape(-1, n)
-        assert rel_fro(u_gpu, out["u"]) <= NS_TOL
-        assert rel_fro(th_gpu - th0.reshape(-1, n), out["theta"] - th0.reshape(-1, n)) <= NS_TOL
+        assert rel_fro(th_gpu - th0.reshape(-1, n), out["theta"] - th0.reshape(-1, n)) <= 1e-5
         assert torch.equal(job.workers[0][gi], job.theta_g[gi]), "write-back must copy theta_g"
     print(f"tiny workload: worst displacement error after H={wl.H} steps {worst:.3e}")
 

@@ -206,6 +206,22 @@ def test_second_quantisation_hand_rows():
     assert np.array_equal(psi, ((a + a).astype(np.float32) + a).astype(np.float32) * third)
 
 
+def test_outer_step_second_stage_is_the_hand_pinned_stage():
+    """The whole outer step with K = 3 must feed its update exactly what requantize_mean (pinned
+    by the hand rows above, including acc * fl32(1/3)) makes of the workers' dequantised values."""
+    r = _rng(23)
+    tg = _f32(r.standard_normal((6, 40)) * 0.02).astype(np.float64)
+    ths = [(_f32(tg) - _f32(r.standard_normal((6, 40)) * 1e-2)).astype(np.float64) for _ in range(3)]
+    u0 = r.standard_normal((6, 40)) * 1e-3
+    for bits in (2, 4, 8):
+        two = diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8, quant_bits=bits, second_quantisation=True)
+        sent = [diloco.dequantize_rowwise(two["q"][k], two["scales"][k]) for k in range(3)]
+        q, s, _ = diloco.requantize_mean(sent, bits)
+        assert np.array_equal(q, two["mean_q"])
+        assert np.array_equal(s.view(np.uint32), two["mean_scales"].view(np.uint32))
+        assert np.array_equal(diloco.dequantize_rowwise(q, s).astype(np.float64), two["psi"])
+
+
 def test_second_quantisation_error_bound_and_use_in_the_update():
     r = _rng(22)
     tg = _f32(r.standard_normal((8, 48)) * 0.02).astype(np.float64)
