@@ -88,12 +88,17 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* p) {
 
 // 16 bytes per lane from rsrc[voff + soff] straight into LDS at lds_off + 16 * lane
 // (lds_off is wavefront-uniform and relative to the workgroup's LDS allocation).
+// The statement writes m0; it is on the clobber list so that the compiler keeps nothing live
+// in it across a transfer (clang notes that m0 is a reserved register: that note is expected).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_off) {
   asm volatile("s_mov_b32 m0, %0\n\t"
                "s_nop 0\n\t"
                "buffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(lds_off), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
