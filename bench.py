@@ -57,10 +57,33 @@ def cpu_baseline(workload, budget_s: float):
         done[f"{m}x{n}"] = done.get(f"{m}x{n}", 0) + 1
         i += 1
     sample = ", ".join(f"{c} of {k}" for k, c in done.items())
-    return {"value": flops / t_used * 1e-12, "unit": "TFLOP/s", "cores": int(cores),
-            "kind": "oracle",
-            "sample": "fp64 NumPy Newton-Schulz (5 iterations) on matrices drawn like the workload's: " + sample,
-            "seconds": round(t_used, 2)}
+    out = {"value": flops / t_used * 1e-12, "unit": "TFLOP/s", "cores": int(cores),
+           "kind": "oracle",
+           "sample": "fp64 NumPy Newton-Schulz (5 iterations) on matrices drawn like the workload's: " + sample,
+           "seconds": round(t_used, 2)}
+    # The elementwise half of the metric: the oracle's outer step (un-quantised, K = 1 and
+    # K = 8, and 4-bit quantised at K = 4) on a slice of 1024 rows of one d x f matrix, priced
+    # with the same algorithmic bytes per element as the GPU figures.
+    from oracle import diloco
+    rows, n = 1024, min(f, 8192)
+    outer = {}
+    for name, K, bits, bpe in (("outer_k1", 1, 0, 4 * 1 + 16), ("outer_k8", 8, 0, 4 * 8 + 16),
+                               ("quantised_outer_k4", 4, 4, 4.5 * 4 + 16 + 4 * 4 / n)):
+        tg_t = S.normal((rows, n), S.PARAM_STD, 0, 2000)
+        tg = tg_t.numpy().astype(np.float64)
+        ths = [(tg_t - S.normal((rows, n), S.DELTA_STD, 0, 2001 + k)).to(S.torch_dtype(workload.param_dtype))
+               .float().numpy().astype(np.float64) for k in range(K)]
+        u0 = np.zeros((rows, n))
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 1.0:
+            diloco.outer_step(tg, u0, ths, eta_out=0.9, mu=0.8, quant_bits=bits)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        outer[name] = {"GBps": rows * n * bpe / dt * 1e-9, "ms_per_call": dt * 1e3, "elements": rows * n}
+    out["outer_step"] = {"unit": "GB/s of algorithmic bytes", "sample": f"{rows} x {n} slice, fp64 NumPy oracle",
+                         **outer}
+    return out
 
 
 def main() -> int:
@@ -120,13 +143,30 @@ def main() -> int:
     torch.cuda.synchronize()
     mlc.muloco_timing_enable(True)
     mlc.muloco_timing_read()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     timing = mlc.muloco_timing_read()
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+
+    # Spread over steps (outside the timed region): the recorder is read after every step, which
+    # synchronises, so that each step's Newton-Schulz launches give a figure of their own.
+    per_step_tf = []
+    for _ in range(args.steps):
+        step()
+        t1 = mlc.muloco_timing_read()["ns_gemm"]
+        if t1["total_ms"] > 0:
+            per_step_tf.append(t1["flops"] / (t1["total_ms"] * 1e-3) * 1e-12)
+    per_step_tf.sort()
     mlc.muloco_timing_enable(False)
+
+    def spread(v):
+        return {"min": v[0], "median": v[len(v) // 2], "max": v[-1]} if v else None
 
     # Outside the timed region: the stand-alone compressor (codes only), so that it has a
     # figure of its own (inside a step it runs fused with the outer update when rows fit in
@@ -186,7 +226,7 @@ def main() -> int:
         torch.cuda.empty_cache()
 
     # Top-k sparsified outer step (5 % kept, error feedback) over the whole model: three selection
-    # passes and the sparsified update; the figure is algorithmic bytes of all four passes.
+    # passes and the sparsified update.
     topk_fig = None
     if job.K * n_elems * 4 + (1 << 30) < torch.cuda.mem_get_info()[0]:
         groups = []
@@ -206,7 +246,13 @@ def main() -> int:
         tt = mlc.muloco_timing_read()["topk"]
         mlc.muloco_timing_enable(False)
         gbs = tt["bytes"] / (tt["total_ms"] * 1e-3) * 1e-9 if tt["total_ms"] > 0 else 0.0
-        topk_fig = {"ms": tt["total_ms"] / 2, "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        # the method's own bytes: one read of theta_k, E_k, theta_g and u and one write of E_k,
+        # theta_g, u and theta_k; the three selection passes are this implementation's cost
+        method_bytes = n_elems * (12 * job.K + 16)
+        mgbs = method_bytes / (tt["total_ms"] / 2 * 1e-3) * 1e-9 if tt["total_ms"] > 0 else 0.0
+        topk_fig = {"ms": tt["total_ms"] / 2, "passes": 4,
+                    "executed_bytes_GBps": gbs, "executed_bytes_frac_hbm": gbs / PEAK_HBM_GBS,
+                    "algorithmic_bytes_GBps": mgbs, "algorithmic_bytes_frac_hbm": mgbs / PEAK_HBM_GBS}
         del groups, wsp
         torch.cuda.empty_cache()
 
@@ -251,6 +297,58 @@ def main() -> int:
     except Exception as e:          # the eager figures stand without it
         graph_ms = f"failed: {e}"
 
+    # The outer-step half of the metric on the configurations it is quoted on (outside the timed
+    # region, outer state only): the fused un-quantised step on the 150M-scale set with K = 8
+    # replicas, and the 4-bit quantised step on the 3.1B-scale shapes with K = 4.
+    n_elems_main, K_main = n_elems, job.K
+    nominal = job.ns_flops() * job.K
+    del job
+    torch.cuda.empty_cache()
+
+    def outer_on(workload_name, quant_bits, reps):
+        w2 = S.WORKLOADS[workload_name]
+        need = w2.n_params() * (2 * w2.K + 8 + (w2.K * quant_bits / 8 if quant_bits else 0)) + (4 << 30)
+        if need > torch.cuda.mem_get_info()[0]:
+            return None
+        j2 = MulocoJob(w2, device="cuda:0", seed=0, with_quant=quant_bits != 0, generate_on="device",
+                       outer_only=True)
+        j2.displace_workers()
+        hp2 = j2.outer_hparams(quant_bits=quant_bits)
+        groups = j2.outer_groups(quant=quant_bits != 0)
+        fam_name = "dequant_outer" if quant_bits else "outer"
+        mlc.muloco_outer_step(groups, hp2)
+        torch.cuda.synchronize()
+        mlc.muloco_timing_enable(True)
+        mlc.muloco_timing_read()
+        per_call = []
+        tot_ms = tot_bytes = 0.0
+        for _ in range(reps):
+            mlc.muloco_outer_step(groups, hp2)
+            t2 = mlc.muloco_timing_read()[fam_name]
+            per_call.append(t2["total_ms"])
+            tot_ms += t2["total_ms"]
+            tot_bytes += t2["bytes"]
+        fig = {"workload": f"{w2.name}-scale, K={w2.K}, {w2.n_params()} elements per replica",
+               "ms": tot_ms / reps, "ms_min": min(per_call), "ms_median": sorted(per_call)[reps // 2],
+               "bytes_per_element": tot_bytes / reps / w2.n_params(),
+               "GBps": tot_bytes / (tot_ms * 1e-3) * 1e-9, "frac_hbm": tot_bytes / (tot_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS}
+        if quant_bits:      # the compressor alone (codes and scales only)
+            mlc.muloco_quantize_delta(groups, hp2)
+            torch.cuda.synchronize()
+            mlc.muloco_timing_read()
+            for _ in range(reps):
+                mlc.muloco_quantize_delta(groups, hp2)
+            tq = mlc.muloco_timing_read()["quantize"]
+            qg = tq["bytes"] / (tq["total_ms"] * 1e-3) * 1e-9 if tq["total_ms"] > 0 else 0.0
+            fig["quantiser_alone"] = {"ms": tq["total_ms"] / reps, "GBps": qg, "frac_hbm": qg / PEAK_HBM_GBS}
+        mlc.muloco_timing_enable(False)
+        del j2, groups
+        torch.cuda.empty_cache()
+        return fig
+
+    outer_k8_150m = outer_on("150m", 0, 10)
+    quantised_outer_k4_31b = outer_on("3.1b", 4, 3)
+
     ms_per_step = wall * 1e3 / args.steps
     gemm = timing["ns_gemm"]
     ns_tflops = gemm["flops"] / (gemm["total_ms"] * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
@@ -269,6 +367,10 @@ def main() -> int:
         "ns_flop_per_step": gemm["flops"] / args.steps,
         "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
         "quantize_outer_fused": fam("dequant_outer"),
+        "outer_k8_150m": outer_k8_150m,
+        "quantised_outer_k4_3.1b": quantised_outer_k4_31b,
+        "step_ms_spread": spread(step_ms),
+        "ns_tflops_per_step_spread": spread(per_step_tf),
         "graph_replay_ms_per_step": graph_ms,
         "adamw_embedding_sized_tensor": adamw_fig,
         "topk_5pct_error_feedback_outer_step_whole_model": topk_fig,
@@ -276,7 +378,6 @@ def main() -> int:
         "quantised_outer_step_whole_model_variants": variants,
         "nominal_ns_tflops_equivalent": None,
     }
-    nominal = job.ns_flops() * job.K
     breakdown["nominal_ns_tflops_equivalent"] = nominal / (gemm["total_ms"] / args.steps * 1e-3) * 1e-12 if gemm["total_ms"] > 0 else 0.0
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"ns_gemm_bf16_kernel_{wl.name}_traffic.txt")
@@ -298,11 +399,14 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}-scale: {wl.layers} layers, d_model {wl.d_model}, FFN {wl.d_ffn}, "
-                               f"K={job.K} replicas, {wl.param_dtype} params, fp32 momentum",
+                               f"K={K_main} replicas, {wl.param_dtype} params, fp32 momentum",
                    "params_2d": wl.n_params(), "ns_iters": 5,
                    "step": "muon inner step + fused outer step + 4-bit quantised outer step per layer fragment"},
         "roofline": {"bound": "mfma", "achieved": ns_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ns_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": (None if traffic is None else
+                                        f"profiles/ns_gemm_bf16_kernel_{wl.name}_traffic.txt (rocprofv3 --pmc runs of this "
+                                        "command; read from the file, not measured in this run)"),
                      # shapes of at most 128 x 512 run the whole chain in one launch instead
                      "kernel": ("ns_chain_small_kernel" if max(wl.d_model, wl.d_ffn) <= 512 and wl.d_model <= 128
                                 else "ns_gemm_bf16_kernel"),
@@ -315,7 +419,8 @@ def main() -> int:
         from paper_2505_23725_amd.build import MICROBENCH_PATH
         res = subprocess.run([MICROBENCH_PATH], capture_output=True, text=True, timeout=120)
         out["achievable"] = json.loads(res.stdout.strip().splitlines()[-1])
-        ach = out["achievable"]["mfma_bf16_tflops_random_operands"]
+        # operands drawn like the workload's; the random-bit-pattern figure is the worst case
+        ach = out["achievable"]["mfma_bf16_tflops_gaussian_operands"]
         out["roofline"]["frac_of_achievable"] = ns_tflops / ach if ach > 0 else None
     except Exception as e:      # the benchmark stands without it
         out["achievable"] = {"error": str(e)}

@@ -21,10 +21,12 @@ class MulocoJob:
                  layers: Optional[int] = None, K: Optional[int] = None,
                  with_quant: bool = False, quant_bits: int = 4, with_ef: bool = False,
                  workspace_cap_bytes: Optional[int] = None,
-                 grad_dtype: Optional[torch.dtype] = None, generate_on: str = "cpu"):
+                 grad_dtype: Optional[torch.dtype] = None, generate_on: str = "cpu",
+                 outer_only: bool = False):
         """generate_on: "cpu" draws every tensor with the CPU generator and copies it over
         (reproducible on the host for parity tests); "device" draws on the GPU (full-size
-        workloads)."""
+        workloads).  outer_only: hold only what the outer step touches (no Muon momentum, no
+        gradients, no Newton-Schulz work space)."""
         self.wl = workload
         self.device = torch.device(device)
         self.seed = seed
@@ -50,15 +52,17 @@ class MulocoJob:
             self.theta_g.append(torch.empty(shp, dtype=torch.float32, device=self.device))
             self.u.append(torch.zeros(shp, dtype=torch.float32, device=self.device))
             self.W.append(torch.empty((self.K,) + tuple(shp), dtype=self.pdtype, device=self.device))
-            self.M.append(torch.zeros((self.K,) + tuple(shp), dtype=torch.float32, device=self.device))
-            self.G.append(torch.zeros((self.K,) + tuple(shp), dtype=self.gdtype, device=self.device))
+            if not outer_only:
+                self.M.append(torch.zeros((self.K,) + tuple(shp), dtype=torch.float32, device=self.device))
+                self.G.append(torch.zeros((self.K,) + tuple(shp), dtype=self.gdtype, device=self.device))
             # theta^(0) in the worker dtype, the same for the global copy and every replica
             self._fill([self.theta_g[gi]] + [self.W[gi][k] for k in range(self.K)], shp,
                        S.PARAM_STD, 100 + gi, self.pdtype)
             for k in range(self.K):
                 self.workers[k].append(self.W[gi][k])
-                self.mom[k].append(self.M[gi][k])
-                self.grad[k].append(self.G[gi][k])
+                if not outer_only:
+                    self.mom[k].append(self.M[gi][k])
+                    self.grad[k].append(self.G[gi][k])
         self.codes = self.scales = self.residuals = None
         self.quant_bits = quant_bits
         if with_quant:
@@ -69,6 +73,9 @@ class MulocoJob:
         if with_ef:      # error-feedback residuals E_k, zero at the start (Algorithm 2)
             self.residuals = [[torch.zeros(shp, dtype=torch.float32, device=self.device)
                                for shp in self.shapes] for _ in range(self.K)]
+        self.workspace = None
+        if outer_only:
+            return
         need = max(B.newton_schulz_workspace_bytes(self.K * s[0], s[1], s[2]) for s in self.shapes)
         floor = max(B.newton_schulz_workspace_min_bytes(s[1], s[2]) for s in self.shapes)
         if workspace_cap_bytes is not None:

@@ -11,7 +11,9 @@ Comparison rules (derived from the arithmetic):
 * Newton-Schulz outputs (bf16 matrix-core path): relative Frobenius error <= 2e-2 per matrix,
   and so that a wrong block cannot hide in the norm of a large matrix: the same ratio on
   every 256 x 256 block of the output (<= 3e-2: a block averages over fewer elements), and
-  the largest element error <= 10 x the rms error and <= a quarter of the largest element.
+  the largest element error <= 16 x the rms error and <= a quarter of the largest element
+  (bf16 rounding errors scale with the element, and elements reach 5-6 x their rms, so the
+  largest error of 1.7e7 elements sits near 10 x the rms error on a correct result).
 * quantiser codes and scales: exact equality.
 """
 import numpy as np
@@ -43,7 +45,7 @@ def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
 
 NS_TILE = 256          # block edge of the per-block check (the GEMM's output tile)
 NS_TILE_TOL = 3e-2
-NS_MAX_OVER_RMS = 10.0
+NS_MAX_OVER_RMS = 16.0
 NS_MAX_FRACTION = 0.25
 
 
@@ -121,7 +123,7 @@ def assert_update_elements(W_gpu_t: torch.Tensor, W_ref: np.ndarray, O_ref: np.n
     """Element-wise bound on the parameters after an inner step, so that a wrong block cannot
     hide in the Frobenius norm of the update: every element must be a storage rounding of a
     value whose orthogonalised term is off by at most UPDATE_ELEMENT_C * max|O| (the element
-    bound of the Newton-Schulz output: 10 x its rms error of 1e-2, with rms(O) about a fifth
+    bound of the Newton-Schulz output: 16 x its rms error of 1e-2, with rms(O) about a fifth
     of max|O|, plus margin).  step = eta * lr_scale.  Returns the worst ratio to the bound."""
     got = to_f64(W_gpu_t)
     half_ulp = storage.bf16_ulp(W_ref) * (0.5 + 2.0 ** -12) if W_gpu_t.dtype == torch.bfloat16 else 0.0
