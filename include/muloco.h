@@ -42,7 +42,8 @@ enum {
   MLC_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or too small */
   MLC_ERR_ARG = -5,         /* scalar argument out of range (iters < 0, K < 1, ...) */
   MLC_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch */
-  MLC_ERR_UNSUPPORTED = -7  /* valid request this build does not implement */
+  MLC_ERR_UNSUPPORTED = -7, /* valid request this build does not implement */
+  MLC_ERR_SCRATCH = -8      /* one matrix does not fit the library's built-in scratch buffer */
 };
 
 #define MLC_MAX_WORKERS 32  /* largest K accepted by the outer step */
@@ -78,6 +79,26 @@ int newton_schulz(const void* in, void* out, int io_dtype,
                   int64_t count, int64_t m, int64_t n,
                   int iters, float a, float b, float c, float eps,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * newton_schulz for callers that cannot allocate device memory or hand over a work space:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * Same operation, arguments and results as newton_schulz, but the work space is a buffer of
+ * MLC_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees
+ * nothing.  The batch is processed in as many chunks as the buffer requires; a shape whose
+ * single matrix needs more (newton_schulz_workspace_min_bytes(m, n) >
+ * MLC_STATIC_SCRATCH_BYTES; 2048 x 2048 still fits, 2048 x 8192 does not) is refused with
+ * MLC_ERR_SCRATCH before anything is enqueued.  Every call on a GPU uses that GPU's one
+ * buffer: calls on different streams of one GPU must not overlap (they would race), calls
+ * on one stream are ordered and need no clearing in between (every byte that is read has
+ * been written earlier in the same call).
+ */
+#define MLC_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int newton_schulz_static_scratch(const void* in, void* out, int io_dtype,
+                                 int64_t count, int64_t m, int64_t n,
+                                 int iters, float a, float b, float c, float eps, void* stream);
 
 /* ------------------------------------------------------------------------------------
  * Muon inner step (paper Sec. 2 "Muon"; Sec. 4.1 eq. 1; Algorithm 1, the Muon line;

@@ -97,6 +97,10 @@ def library() -> C.CDLL:
     lib.newton_schulz.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64,
                                   C.c_int, C.c_float, C.c_float, C.c_float, C.c_float,
                                   C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.newton_schulz_static_scratch.restype = C.c_int
+    lib.newton_schulz_static_scratch.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64,
+                                                 C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
+                                                 C.c_float, C.c_void_p]
     for name in ("muloco_inner_workspace_bytes", "muloco_inner_workspace_min_bytes"):
         f = getattr(lib, name)
         f.restype = C.c_size_t
@@ -329,6 +333,22 @@ def newton_schulz(inp: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
                                  _dev_ptr(workspace, "workspace"),
                                  workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "newton_schulz")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def newton_schulz_static_scratch(inp: torch.Tensor, out: torch.Tensor, iters: int = 5, a: float = 3.4445,
+                                 b: float = -4.7750, c: float = 2.0315, eps: float = 1e-7,
+                                 stream=None) -> torch.Tensor:
+    """newton_schulz in the library's built-in scratch buffer: allocates nothing."""
+    cnt, m, n = _shape3(inp)
+    if tuple(out.shape) != tuple(inp.shape) or out.dtype != inp.dtype:
+        raise ValueError("out must match inp in shape and dtype")
+    rc = library().newton_schulz_static_scratch(_dev_ptr(inp, "inp"), _dev_ptr(out, "out"), _dtype_code(inp),
+                                                cnt, m, n, int(iters), a, b, c, eps, _stream(stream))
+    _check(rc, "newton_schulz_static_scratch")
     return out
 
 

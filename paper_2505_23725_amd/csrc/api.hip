@@ -7,6 +7,10 @@
 
 #include "common.h"
 
+// Work space of newton_schulz_static_scratch.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address differs per GPU and is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[MLC_STATIC_SCRATCH_BYTES];
+
 namespace mlc {
 
 // ---- timing recorder -------------------------------------------------------------
@@ -225,6 +229,7 @@ const char* muloco_strerror(int code) {
     case MLC_ERR_ARG: return "argument out of range";
     case MLC_ERR_LAUNCH: return "kernel launch failed";
     case MLC_ERR_UNSUPPORTED: return "unsupported combination";
+    case MLC_ERR_SCRATCH: return "one matrix of this shape does not fit the built-in scratch buffer";
     default: return "unknown error";
   }
 }
@@ -240,19 +245,15 @@ size_t newton_schulz_workspace_bytes(int64_t count, int64_t m, int64_t n) {
   return make_plan(m, n).per_matrix * (size_t)c;
 }
 
-int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_t m, int64_t n,
-                  int iters, float a, float b, float c, float eps, void* workspace,
-                  size_t workspace_bytes, void* stream_) {
-  if (!in || !out) return MLC_ERR_NULL;
-  if (!valid_dtype(io_dtype)) return MLC_ERR_DTYPE;
-  int rc = check_shape(count, m, n);
-  if (rc != MLC_OK) return rc;
-  if (iters < 0 || !(eps >= 0.f)) return MLC_ERR_ARG;
-  if (!aligned16(in) || !aligned16(out)) return MLC_ERR_ARG;
+// Shared body of newton_schulz and newton_schulz_static_scratch; `need_error` is the code
+// returned when the work space cannot hold one matrix.
+static int newton_schulz_in(const void* in, void* out, int io_dtype, int64_t count, int64_t m, int64_t n,
+                            int iters, float a, float b, float c, float eps, void* workspace,
+                            size_t workspace_bytes, int need_error, hipStream_t stream) {
   const NsPlan p = make_plan(m, n);
-  rc = check_workspace(workspace, workspace_bytes, p.per_matrix);
+  if (workspace_bytes < p.per_matrix) return need_error;
+  int rc = check_workspace(workspace, workspace_bytes, p.per_matrix);
   if (rc != MLC_OK) return rc;
-  hipStream_t stream = (hipStream_t)stream_;
   const int64_t chunk = chunk_for(p, workspace_bytes, count);
   const size_t es = elem_size(io_dtype);
   for (int64_t c0 = 0; c0 < count; c0 += chunk) {
@@ -270,6 +271,54 @@ int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_
     if (rc != MLC_OK) return rc;
   }
   return MLC_OK;
+}
+
+static int check_ns_args(const void* in, const void* out, int io_dtype, int64_t count, int64_t m,
+                         int64_t n, int iters, float eps) {
+  if (!in || !out) return MLC_ERR_NULL;
+  if (!valid_dtype(io_dtype)) return MLC_ERR_DTYPE;
+  const int rc = check_shape(count, m, n);
+  if (rc != MLC_OK) return rc;
+  if (iters < 0 || !(eps >= 0.f)) return MLC_ERR_ARG;
+  if (!aligned16(in) || !aligned16(out)) return MLC_ERR_ARG;
+  return MLC_OK;
+}
+
+int newton_schulz(const void* in, void* out, int io_dtype, int64_t count, int64_t m, int64_t n,
+                  int iters, float a, float b, float c, float eps, void* workspace,
+                  size_t workspace_bytes, void* stream_) {
+  const int rc = check_ns_args(in, out, io_dtype, count, m, n, iters, eps);
+  if (rc != MLC_OK) return rc;
+  if (!workspace) return MLC_ERR_WORKSPACE;
+  return newton_schulz_in(in, out, io_dtype, count, m, n, iters, a, b, c, eps, workspace, workspace_bytes,
+                          MLC_ERR_WORKSPACE, (hipStream_t)stream_);
+}
+
+// Device address of `scratch` on the current device, looked up on the first call there.
+static int static_scratch_address(void** out) {
+  static std::atomic<void*> address[MAX_DEVICES];
+  const int slot = device_slot();
+  if (slot < 0) return MLC_ERR_UNSUPPORTED;
+  void* p = address[slot].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MLC_ERR_LAUNCH;
+    address[slot].store(p, std::memory_order_release);   // two threads racing store the same value
+  }
+  *out = p;
+  return MLC_OK;
+}
+
+int newton_schulz_static_scratch(const void* in, void* out, int io_dtype, int64_t count, int64_t m,
+                                 int64_t n, int iters, float a, float b, float c, float eps,
+                                 void* stream_) {
+  int rc = check_ns_args(in, out, io_dtype, count, m, n, iters, eps);
+  if (rc != MLC_OK) return rc;
+  if (make_plan(m, n).per_matrix > MLC_STATIC_SCRATCH_BYTES) return MLC_ERR_SCRATCH;
+  void* ws = nullptr;
+  rc = static_scratch_address(&ws);
+  if (rc != MLC_OK) return rc;
+  return newton_schulz_in(in, out, io_dtype, count, m, n, iters, a, b, c, eps, ws, MLC_STATIC_SCRATCH_BYTES,
+                          MLC_ERR_SCRATCH, (hipStream_t)stream_);
 }
 
 static int check_inner_groups(const mlc_inner_group* groups, int n_groups) {

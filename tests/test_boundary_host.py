@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_and_codes():
     assert mlc.strerror(0) == "ok"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert mlc.strerror(code) not in ("ok", "unknown error")
     assert mlc.strerror(-99) == "unknown error"
 
@@ -54,6 +54,25 @@ def test_workspace_sizes():
 
 def _ns(lib, inp=0x1000, out=0x1000, dtype=0, count=1, m=128, n=128, iters=5, ws=0x10000, wsb=1 << 30, eps=1e-7):
     return lib.newton_schulz(inp, out, dtype, count, m, n, iters, 3.4445, -4.775, 2.0315, eps, ws, wsb, None)
+
+
+def test_static_scratch_entry_rejects_before_touching_the_gpu():
+    lib = mlc.library()
+
+    def call(inp=0x1000, out=0x1000, dtype=1, count=1, m=128, n=128, iters=5, eps=1e-7):
+        return lib.newton_schulz_static_scratch(inp, out, dtype, count, m, n, iters, 3.4445, -4.775, 2.0315,
+                                                eps, None)
+    assert call(inp=None) == -1
+    assert call(dtype=9) == -3
+    assert call(count=0) == -2
+    assert call(iters=-1) == -5
+    assert call(out=0x1008) == -5
+    # one 2048 x 8192 matrix needs more than the built-in buffer; 2048 x 2048 is the largest square
+    assert mlc.newton_schulz_workspace_min_bytes(2048, 8192) > B.STATIC_SCRATCH_BYTES
+    assert mlc.newton_schulz_workspace_min_bytes(2048, 2048) <= B.STATIC_SCRATCH_BYTES
+    assert call(m=2048, n=8192) == -8
+    assert call(m=8192, n=2048, count=3) == -8
+    assert "scratch" in mlc.strerror(-8)
 
 
 def test_newton_schulz_argument_errors():

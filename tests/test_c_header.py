@@ -20,6 +20,7 @@ typedef void (*any_fn)(void);
 static const any_fn entry_points[] = {
   (any_fn)muloco_strerror, (any_fn)newton_schulz_workspace_bytes,
   (any_fn)newton_schulz_workspace_min_bytes, (any_fn)newton_schulz,
+  (any_fn)newton_schulz_static_scratch,
   (any_fn)muloco_inner_workspace_bytes, (any_fn)muloco_inner_workspace_min_bytes,
   (any_fn)muloco_inner_step, (any_fn)muloco_outer_step, (any_fn)muloco_quantize_delta,
   (any_fn)muloco_topk_workspace_bytes, (any_fn)muloco_topk_outer_step,
@@ -31,7 +32,7 @@ int main(void) {
   mlc_adamw_hparams ah = {0};
   mlc_kernel_timing t[MLC_KERNEL_FAMILIES];
   (void)hp; (void)mh; (void)ah; (void)t;
-  return entry_points[0] == NULL || sizeof(entry_points) / sizeof(entry_points[0]) != 14;
+  return entry_points[0] == NULL || sizeof(entry_points) / sizeof(entry_points[0]) != 15;
 }
 """
 
@@ -78,7 +79,8 @@ def test_binding_structures_match_the_header_field_by_field():
             lines.append(f'  printf("{cname} {fname} %zu %zu\\n", offsetof({cname}, {fname}), '
                          f'sizeof((({cname}*)0)->{fname}));')
     lines.append('  printf("const MLC_MAX_WORKERS %d\\nconst MLC_KERNEL_FAMILIES %d\\nconst MLC_F32 %d\\n'
-                 'const MLC_BF16 %d\\n", MLC_MAX_WORKERS, (int)MLC_KERNEL_FAMILIES, (int)MLC_F32, (int)MLC_BF16);')
+                 'const MLC_BF16 %d\\nconst MLC_STATIC_SCRATCH_BYTES %zu\\n", MLC_MAX_WORKERS, (int)MLC_KERNEL_FAMILIES, (int)MLC_F32, '
+                 '(int)MLC_BF16, (size_t)MLC_STATIC_SCRATCH_BYTES);')
     lines += ["  return 0;", "}"]
     with tempfile.TemporaryDirectory() as tmp:
         src = os.path.join(tmp, "layout.c")
@@ -95,7 +97,8 @@ def test_binding_structures_match_the_header_field_by_field():
         if parts[0] == "const":
             expected = {"MLC_MAX_WORKERS": binding.MLC_MAX_WORKERS,
                         "MLC_KERNEL_FAMILIES": len(binding.KERNEL_FAMILIES),
-                        "MLC_F32": binding.MLC_F32, "MLC_BF16": binding.MLC_BF16}[parts[1]]
+                        "MLC_F32": binding.MLC_F32, "MLC_BF16": binding.MLC_BF16,
+                        "MLC_STATIC_SCRATCH_BYTES": binding.STATIC_SCRATCH_BYTES}[parts[1]]
             assert int(parts[2]) == expected, line
             continue
         st = getattr(binding, STRUCTS[parts[0]])
