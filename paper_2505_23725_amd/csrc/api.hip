@@ -496,12 +496,47 @@ int muloco_quantize_delta(const mlc_outer_group* groups, int n_groups, const mlc
   return MLC_OK;
 }
 
+// Can this group go into a launch that covers several groups?
+static bool multi_launch_covers(const mlc_outer_group& g, const mlc_outer_hparams& hp) {
+  if (hp.K > OUTER_MAX_SEG_K || hp.second_quantisation || hp.quant_per_matrix) return false;
+  if (hp.quant_bits == 0) return true;
+  const int cfg = quant_reg_cfg(g.n);
+  return cfg >= 0 && cfg <= QUANT_MULTI_MAX_CFG && !(g.worker_dtype == MLC_F32 && g.global_dtype == MLC_BF16);
+}
+
 int muloco_outer_step(const mlc_outer_group* groups, int n_groups, const mlc_outer_hparams* hp,
                       void* stream_) {
   int rc = check_outer(groups, n_groups, hp, true);
   if (rc != MLC_OK) return rc;
   hipStream_t stream = (hipStream_t)stream_;
   for (int i = 0; i < n_groups; ++i) {
+    // Consecutive groups of one dtype pair share a launch (a streaming fragment of one layer
+    // is three small groups: one launch instead of three fills the chip for longer).
+    int run = 0;
+    while (i + run < n_groups && run < OUTER_MAX_SEG && groups[i + run].worker_dtype == groups[i].worker_dtype &&
+           groups[i + run].global_dtype == groups[i].global_dtype && multi_launch_covers(groups[i + run], *hp))
+      ++run;
+    if (run >= 2) {
+      OuterGroupArgs args[OUTER_MAX_SEG];
+      for (int j = 0; j < run; ++j) {
+        const mlc_outer_group& g = groups[i + j];
+        OuterPtrs p;
+        gather_ptrs(g, *hp, p);
+        args[j].w = p.w; args[j].codes = p.c; args[j].scales = p.s; args[j].offsets = p.o; args[j].ef = p.e;
+        args[j].theta_g = g.global_param; args[j].u = g.outer_momentum;
+        args[j].rows = g.count * g.m; args[j].n = g.n;
+      }
+      if (hp->quant_bits)
+        rc = launch_quantize_outer_multi(args, run, groups[i].worker_dtype, groups[i].global_dtype, hp->K,
+                                         form_of(groups[i], *hp), hp->eta_out, hp->mu, hp->nesterov,
+                                         hp->write_back, stream);
+      else
+        rc = launch_outer_fused_multi(args, run, groups[i].worker_dtype, groups[i].global_dtype, hp->K,
+                                      hp->eta_out, hp->mu, hp->nesterov, hp->write_back, stream);
+      if (rc != MLC_OK) return rc;
+      i += run - 1;
+      continue;
+    }
     const mlc_outer_group& g = groups[i];
     OuterPtrs p;
     gather_ptrs(g, *hp, p);

@@ -124,6 +124,25 @@ int launch_outer_fused(const WorkerPtrs& w, int worker_dtype, void* theta_g, int
                        int write_back, hipStream_t stream);
 // residual (error-feedback) accumulators per worker; all null = no error feedback
 struct ResidualPtrs { float* p[MLC_MAX_WORKERS]; };
+// Several groups in one launch: at most this many groups and workers (their table travels
+// in the kernel arguments).
+constexpr int OUTER_MAX_SEG = 4;
+constexpr int OUTER_MAX_SEG_K = 8;
+struct OuterGroupArgs {
+  WorkerPtrs w; CodePtrs codes; ScalePtrs scales; ScalePtrs offsets; ResidualPtrs ef;
+  void* theta_g; float* u; int64_t rows, n;
+};
+// >= 0 when the one-pass quantiser covers rows of length n; rows up to 8192 columns
+// (configurations 0 .. QUANT_MULTI_MAX_CFG) can share a launch with other groups, longer ones
+// need so many registers per thread that they would halve the occupancy of the whole launch.
+int quant_reg_cfg(int64_t n);
+constexpr int QUANT_MULTI_MAX_CFG = 4;
+struct QuantForm;
+int launch_outer_fused_multi(const OuterGroupArgs* gs, int ng, int worker_dtype, int global_dtype, int K,
+                             float eta_out, float mu, int nesterov, int write_back, hipStream_t stream);
+int launch_quantize_outer_multi(const OuterGroupArgs* gs, int ng, int worker_dtype, int global_dtype, int K,
+                                const QuantForm& form, float eta_out, float mu, int nesterov, int write_back,
+                                hipStream_t stream);
 // Radix-select state of one (worker, matrix) pair of the top-k sparsifier.
 constexpr int TOPK_BINS = 2048;     // widest digit of the radix select: 11 bits
 struct TopkState { unsigned int hist[TOPK_BINS]; unsigned int prefix, mask, rank, pad; };

@@ -29,6 +29,17 @@ template <> struct Ld<float> {
   static __device__ __forceinline__ float load1(const float* p) { return *p; }
   static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
   static __device__ __forceinline__ float round(float v) { return v; }   // value as stored
+  // 8 values as they sit in memory (held back while earlier values are worked on)
+  struct raw_t { f32x4 a, b; };
+  static __device__ __forceinline__ raw_t load_raw(const float* p) {
+    raw_t r;
+    r.a = *reinterpret_cast<const f32x4*>(p);
+    r.b = *reinterpret_cast<const f32x4*>(p + 4);
+    return r;
+  }
+  static __device__ __forceinline__ void unpack(const raw_t& r, float (&v)[8]) {
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+  }
 };
 template <> struct Ld<bf16_t> {
   static __device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
@@ -45,6 +56,12 @@ template <> struct Ld<bf16_t> {
   static __device__ __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(*p); }
   static __device__ __forceinline__ void store1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
   static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+  typedef u32x4 raw_t;
+  static __device__ __forceinline__ raw_t load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+  static __device__ __forceinline__ void unpack(const raw_t& w, float (&v)[8]) {
+    v[0] = bf16lo(w.x); v[1] = bf16hi(w.x); v[2] = bf16lo(w.y); v[3] = bf16hi(w.y);
+    v[4] = bf16lo(w.z); v[5] = bf16hi(w.z); v[6] = bf16lo(w.w); v[7] = bf16hi(w.w);
+  }
 };
 
 // eq. 3; theta comes back as the value the global buffer will hold after the store, so the
@@ -58,13 +75,13 @@ __device__ __forceinline__ void outer_update(float& theta, float& u, float psi, 
 }
 
 // ---- unquantised fused outer step ---------------------------------------------------
-template <typename WT, typename GT>
-__global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
-    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, long n_elems, int K, float eta,
-    float mu, float inv_k, int nesterov, int write_back) {
+// Workgroup blk of nblk walks over its share of the n_elems elements.
+template <typename WT, typename GT, typename PW>
+__device__ __forceinline__ void outer_fused_body(
+    const PW& w, GT* __restrict__ theta_g, float* __restrict__ u, long n_elems, int K, float eta,
+    float mu, float inv_k, int nesterov, int write_back, long blk, long nblk) {
   const long n_vec = n_elems / 8;
-  for (long i = (long)blockIdx.x * OT_THREADS + threadIdx.x; i < n_vec;
-       i += (long)gridDim.x * OT_THREADS) {
+  for (long i = blk * OT_THREADS + threadIdx.x; i < n_vec; i += nblk * OT_THREADS) {
     const long off = i * 8;
     float tg[8], uv[8], acc[8];
     Ld<GT>::load8(theta_g + off, tg);
@@ -86,7 +103,7 @@ __global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
   }
   // ragged tail (fewer than 8 elements), one thread each
   const long tail0 = n_vec * 8;
-  const long t = tail0 + (long)blockIdx.x * OT_THREADS + threadIdx.x;
+  const long t = tail0 + blk * OT_THREADS + threadIdx.x;
   if (t < n_elems) {
     float tg = Ld<GT>::load1(theta_g + t), uv = u[t], acc = 0.f;
     for (int k = 0; k < K; ++k) acc += tg - Ld<WT>::load1(reinterpret_cast<const WT*>(w.p[k]) + t);
@@ -96,6 +113,14 @@ __global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
     if (write_back)
       for (int k = 0; k < K; ++k) Ld<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + t, tg);
   }
+}
+
+template <typename WT, typename GT>
+__global__ __launch_bounds__(OT_THREADS) void outer_fused_kernel(
+    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, long n_elems, int K, float eta,
+    float mu, float inv_k, int nesterov, int write_back) {
+  outer_fused_body<WT, GT>(w, theta_g, u, n_elems, K, eta, mu, inv_k, nesterov, write_back,
+                           (long)blockIdx.x, (long)gridDim.x);
 }
 
 // ---- linear quantiser (Sec. 2 "Compressed Communication"; Algorithm 2) -----------------
@@ -176,7 +201,8 @@ __device__ __forceinline__ void load_levels8(const uint8_t* crow, int c, int (&q
 }
 
 // Range of worker k's row (or of the matrix the row belongs to) as stored by an earlier pass.
-__device__ __forceinline__ Range stored_range(const ScalePtrs& scales, const OffsetPtrs& offsets, int k,
+template <typename PS, typename PO>
+__device__ __forceinline__ Range stored_range(const PS& scales, const PO& offsets, int k,
                                               long grp, const QuantForm& f) {
   Range r;
   r.scale = scales.p[k][grp];
@@ -347,18 +373,22 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
 // for all K workers and every theta_k exactly once.  Same arithmetic as above.  With
 // OUTER the dequantised values go straight into the mean and eq. 3 without re-reading
 // theta_g or the codes; codes, scales and offsets are written either way.
-template <typename WT, typename GT, int NV, int G, bool OUTER>
-__global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
-    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
-    OffsetPtrs offsets, ResidualPtrs ef, long rows, int n, int K, QuantForm form, float eta, float mu,
+// `blk` is the index of the workgroup among those that share these arguments; the pointer sets
+// may be the 32-wide ones of a single-group launch or the narrow ones of a launch that covers
+// several groups.
+template <typename WT, typename GT, int NV, int G, bool OUTER, typename PW, typename PC, typename PS,
+          typename PO, typename PE>
+__device__ __forceinline__ void quantize_rows_reg_body(
+    const PW& w, GT* __restrict__ theta_g, float* __restrict__ u, const PC& codes, const PS& scales,
+    const PO& offsets, const PE& ef, long rows, int n, int K, const QuantForm& form, float eta, float mu,
     float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes, float* mean_scales,
-    float* mean_offsets) {
+    float* mean_offsets, long blk) {
   constexpr int ROWS_PER_BLOCK = OT_THREADS / G;
   constexpr int NW = OT_THREADS / 64;
   __shared__ float red[2][2][NW];          // [parity of k][min, max][wavefront]
   __shared__ float red2[2][NW];
   const int t = threadIdx.x % G;
-  const long row = (long)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / G;
+  const long row = blk * ROWS_PER_BLOCK + threadIdx.x / G;
   const bool live = row < rows;            // whole groups are live or not; no early return
   const long rbase = live ? row * n : 0;   // (the workgroup-wide barrier below needs everyone)
   const int bits = form.bits;
@@ -376,17 +406,33 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
   }
-  for (int k = 0; k < K; ++k) {
+  // The next worker's row is requested before this worker's row is reduced and quantised, so
+  // that with several workers only the first request waits for memory with nothing to do.
+  typedef typename Ld<WT>::raw_t RawT;
+  RawT ahead[NV];
+  auto request = [&](int k) {
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (t + i * G) * 8;
+      if (live && c < n) ahead[i] = Ld<WT>::load_raw(tk + c);
+    }
+  };
+  request(0);
+  for (int k = 0; k < K; ++k) {
     float* res = ef.p[k] ? ef.p[k] + rbase : nullptr;
     float d[NV][8];
     float mn = INFINITY, mx = -INFINITY;
+    RawT cur[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) cur[i] = ahead[i];
+    if (k + 1 < K) request(k + 1);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
       if (live && c < n) {
         float b[8];
-        Ld<WT>::load8(tk + c, b);
+        Ld<WT>::unpack(cur[i], b);
 #pragma unroll
         for (int j = 0; j < 8; ++j) d[i][j] = tg[i][j] - b[j];
         if (res) {
@@ -495,6 +541,88 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
       }
     }
   }
+}
+
+template <typename WT, typename GT, int NV, int G, bool OUTER>
+__global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
+    WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
+    OffsetPtrs offsets, ResidualPtrs ef, long rows, int n, int K, QuantForm form, float eta, float mu,
+    float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes, float* mean_scales,
+    float* mean_offsets) {
+  quantize_rows_reg_body<WT, GT, NV, G, OUTER>(w, theta_g, u, codes, scales, offsets, ef, rows, n, K, form,
+                                               eta, mu, inv_k, nesterov, write_back, requant, mean_codes,
+                                               mean_scales, mean_offsets, (long)blockIdx.x);
+}
+
+// ---- one launch over several groups ----------------------------------------------------
+// A streaming fragment (one transformer layer: three shape groups) is small enough that
+// three launches of 70-80 us each spend a good part of their time filling and draining the
+// chip; here the workgroups of one launch are dealt to the groups of a table that travels in
+// the kernel arguments (up to OUTER_MAX_SEG groups, OUTER_MAX_SEG_K workers).
+template <typename T> struct SegPtrs { T p[OUTER_MAX_SEG_K]; };
+struct QuantSeg {
+  SegPtrs<void*> w;
+  SegPtrs<uint8_t*> codes;
+  SegPtrs<float*> scales, offsets, ef;
+  void* theta_g;
+  float* u;
+  long rows;
+  int n;
+  int cfg;                  // index into the (vectors per thread, threads per row) table below
+  unsigned int blk0;        // first workgroup of this group
+};
+struct QuantSegTable { QuantSeg s[OUTER_MAX_SEG]; int nseg; };
+
+// (NV, G) of a row length, as launch_quantize_outer_fused picks them; -1: not covered
+struct RegCfg { int nv, g; };
+__host__ __device__ constexpr RegCfg reg_cfg(int idx) {
+  return idx == 0 ? RegCfg{1, 64} : idx == 1 ? RegCfg{2, 64} : idx == 2 ? RegCfg{4, 64}
+       : idx == 3 ? RegCfg{2, 256} : idx == 4 ? RegCfg{4, 256} : idx == 5 ? RegCfg{6, 256}
+       : idx == 6 ? RegCfg{8, 256} : RegCfg{12, 256};
+}
+
+template <typename WT, typename GT>
+__global__ __launch_bounds__(OT_THREADS) void quantize_outer_multi_kernel(
+    QuantSegTable tab, int K, QuantForm form, float eta, float mu, float inv_k, int nesterov, int write_back) {
+  int si = 0;
+#pragma unroll
+  for (int i = 1; i < OUTER_MAX_SEG; ++i)
+    if (i < tab.nseg && blockIdx.x >= tab.s[i].blk0) si = i;
+  const QuantSeg& sg = tab.s[si];
+  const long blk = (long)(blockIdx.x - sg.blk0);
+#define MLC_SEG_BODY(IDX)                                                                              \
+  quantize_rows_reg_body<WT, GT, reg_cfg(IDX).nv, reg_cfg(IDX).g, true>(                               \
+      sg.w, (GT*)sg.theta_g, sg.u, sg.codes, sg.scales, sg.offsets, sg.ef, sg.rows, sg.n, K, form, eta, \
+      mu, inv_k, nesterov, write_back, 0, nullptr, nullptr, nullptr, blk)
+  switch (sg.cfg) {      // uniform over the workgroup
+    case 0: MLC_SEG_BODY(0); break;
+    case 1: MLC_SEG_BODY(1); break;
+    case 2: MLC_SEG_BODY(2); break;
+    case 3: MLC_SEG_BODY(3); break;
+    default: MLC_SEG_BODY(4); break;      // rows that need more vectors per thread (and with
+  }                                        // them more registers) are not taken: see the launcher
+#undef MLC_SEG_BODY
+}
+
+struct OuterSeg {
+  SegPtrs<void*> w;
+  void* theta_g;
+  float* u;
+  long n_elems;
+  unsigned int blk0, nblk;
+};
+struct OuterSegTable { OuterSeg s[OUTER_MAX_SEG]; int nseg; };
+
+template <typename WT, typename GT>
+__global__ __launch_bounds__(OT_THREADS) void outer_fused_multi_kernel(
+    OuterSegTable tab, int K, float eta, float mu, float inv_k, int nesterov, int write_back) {
+  int si = 0;
+#pragma unroll
+  for (int i = 1; i < OUTER_MAX_SEG; ++i)
+    if (i < tab.nseg && blockIdx.x >= tab.s[i].blk0) si = i;
+  const OuterSeg& sg = tab.s[si];
+  outer_fused_body<WT, GT>(sg.w, (GT*)sg.theta_g, sg.u, sg.n_elems, K, eta, mu, inv_k, nesterov, write_back,
+                           (long)(blockIdx.x - sg.blk0), (long)sg.nblk);
 }
 
 // ---- dequantise + average + outer update --------------------------------------------
@@ -945,6 +1073,105 @@ int launch_quantize_outer_fused(const WorkerPtrs& w, int worker_dtype, void* the
   else MLC_QO_NV(float, float);
 #undef MLC_QO_NV
 #undef MLC_QO
+  return check_launch();
+}
+
+// One launch for the fused un-quantised outer step of up to OUTER_MAX_SEG groups.
+int launch_outer_fused_multi(const OuterGroupArgs* gs, int ng, int worker_dtype, int global_dtype, int K,
+                             float eta_out, float mu, int nesterov, int write_back, hipStream_t stream) {
+  if (ng < 1 || ng > OUTER_MAX_SEG || K > OUTER_MAX_SEG_K) return MLC_ERR_UNSUPPORTED;
+  OuterSegTable tab;
+  tab.nseg = ng;
+  double total = 0.0;
+  for (int i = 0; i < ng; ++i) total += (double)gs[i].rows * (double)gs[i].n;
+  // about 16 workgroups per compute unit in all, dealt in proportion to the groups' sizes
+  const double budget = 256.0 * 16.0;
+  unsigned int blk = 0;
+  double bytes = 0.0;
+  for (int i = 0; i < OUTER_MAX_SEG; ++i) {
+    OuterSeg& sg = tab.s[i];
+    if (i >= ng) { sg = tab.s[0]; sg.blk0 = 0xffffffffu; sg.nblk = 0; continue; }
+    const long n_elems = gs[i].rows * gs[i].n;
+    for (int k = 0; k < OUTER_MAX_SEG_K; ++k) sg.w.p[k] = k < K ? gs[i].w.p[k] : nullptr;
+    sg.theta_g = gs[i].theta_g;
+    sg.u = gs[i].u;
+    sg.n_elems = n_elems;
+    const long want = (n_elems / 8 + OT_THREADS - 1) / OT_THREADS;
+    long nb = (long)(budget * (double)n_elems / total + 0.5);
+    if (nb > want) nb = want;
+    if (nb < 1) nb = 1;
+    sg.blk0 = blk;
+    sg.nblk = (unsigned int)nb;
+    blk += (unsigned int)nb;
+    bytes += (double)n_elems * (K * esize(worker_dtype) * (write_back ? 2 : 1) + 2 * esize(global_dtype) + 8);
+  }
+  LaunchScope scope(MLC_KERNEL_OUTER, stream, 0.0, bytes);
+  const float inv_k = 1.0f / (float)K;
+#define MLC_CALL(WT, GT)                                                                              \
+  hipLaunchKernelGGL((outer_fused_multi_kernel<WT, GT>), dim3(blk), dim3(OT_THREADS), 0, stream, tab, K, \
+                     eta_out, mu, inv_k, nesterov, write_back)
+  MLC_DISPATCH2(worker_dtype, global_dtype, MLC_CALL);
+#undef MLC_CALL
+  return check_launch();
+}
+
+// Index of the (vectors per thread, threads per row) pair of the one-pass kernel for rows of
+// length n, or -1 when the one-pass kernel does not cover them.
+int quant_reg_cfg(int64_t n) {
+  if (n % 8 || n > 24576) return -1;
+  const int g = n <= 2048 ? 64 : OT_THREADS;
+  const int need = (int)((n + g * 8 - 1) / (g * 8));
+  if (g == 64) return need <= 1 ? 0 : need <= 2 ? 1 : 2;
+  return need <= 2 ? 3 : need <= 4 ? 4 : need <= 6 ? 5 : need <= 8 ? 6 : 7;
+}
+
+// One launch for the quantised outer step (quantise + dequantise + mean + eq. 3 + write-back)
+// of up to OUTER_MAX_SEG groups; ranges per row, no second quantisation.
+int launch_quantize_outer_multi(const OuterGroupArgs* gs, int ng, int worker_dtype, int global_dtype, int K,
+                                const QuantForm& form, float eta_out, float mu, int nesterov, int write_back,
+                                hipStream_t stream) {
+  if (ng < 1 || ng > OUTER_MAX_SEG || K > OUTER_MAX_SEG_K || form.rows_per_range != 0) return MLC_ERR_UNSUPPORTED;
+  if (worker_dtype == MLC_F32 && global_dtype == MLC_BF16) return MLC_ERR_UNSUPPORTED;
+  QuantSegTable tab;
+  tab.nseg = ng;
+  unsigned long blk = 0;
+  double bytes = 0.0;
+  bool ef_any = false;
+  for (int i = 0; i < OUTER_MAX_SEG; ++i) {
+    QuantSeg& sg = tab.s[i];
+    if (i >= ng) { sg = tab.s[0]; sg.blk0 = 0xffffffffu; continue; }
+    const int cfg = quant_reg_cfg(gs[i].n);
+    if (cfg < 0 || cfg > QUANT_MULTI_MAX_CFG) return MLC_ERR_UNSUPPORTED;
+    for (int k = 0; k < OUTER_MAX_SEG_K; ++k) {
+      sg.w.p[k] = k < K ? gs[i].w.p[k] : nullptr;
+      sg.codes.p[k] = k < K ? gs[i].codes.p[k] : nullptr;
+      sg.scales.p[k] = k < K ? gs[i].scales.p[k] : nullptr;
+      sg.offsets.p[k] = k < K ? gs[i].offsets.p[k] : nullptr;
+      sg.ef.p[k] = k < K ? gs[i].ef.p[k] : nullptr;
+    }
+    ef_any = gs[i].ef.p[0] != nullptr;
+    sg.theta_g = gs[i].theta_g;
+    sg.u = gs[i].u;
+    sg.rows = gs[i].rows;
+    sg.n = (int)gs[i].n;
+    sg.cfg = cfg;
+    const long rpb = OT_THREADS / reg_cfg(cfg).g;
+    sg.blk0 = (unsigned int)blk;
+    blk += (unsigned long)((gs[i].rows + rpb - 1) / rpb);
+    if (blk > 0x7fffffffUL) return MLC_ERR_SHAPE;
+    bytes += (double)gs[i].rows * gs[i].n * (K * esize(worker_dtype) * (write_back ? 2 : 1) + form.bits / 8.0 * K +
+                                             (ef_any ? 8.0 * K : 0.0) + 2 * esize(global_dtype) + 8) +
+             (double)gs[i].rows * 4 * K;
+  }
+  LaunchScope scope(MLC_KERNEL_DEQUANT_OUTER, stream, 0.0, bytes);
+  const float inv_k = 1.0f / (float)K;
+#define MLC_QM(WT, GT)                                                                             \
+  hipLaunchKernelGGL((quantize_outer_multi_kernel<WT, GT>), dim3((unsigned)blk), dim3(OT_THREADS), 0, \
+                     stream, tab, K, form, eta_out, mu, inv_k, nesterov, write_back)
+  if (worker_dtype == MLC_BF16 && global_dtype == MLC_F32) MLC_QM(bf16_t, float);
+  else if (worker_dtype == MLC_BF16) MLC_QM(bf16_t, bf16_t);
+  else MLC_QM(float, float);
+#undef MLC_QM
   return check_launch();
 }
 

@@ -147,3 +147,43 @@ def test_special_cases_on_gpu():
     torch.cuda.synchronize()
     mean = np.mean([to_f64(w) for w in ws0], axis=0)
     assert_fp32_close(tg.cpu(), mean, "plain averaging")
+
+
+@pytest.mark.parametrize("quant_bits,ef", [(0, False), (4, False), (4, True), (8, False), (2, True)])
+@pytest.mark.parametrize("K", [2, 8, 9])
+def test_several_groups_in_one_call_equal_one_call_per_group(quant_bits, ef, K):
+    """A call with several groups takes them in one launch (up to 4 groups, 8 workers; K = 9
+    falls back to a launch per group).  Every output must carry the bits that a call per group
+    gives: row lengths cover the wavefront-per-row and the workgroup-per-row kernels, ragged
+    row counts, and for the un-quantised step a ragged flat tail."""
+    shapes = [(3, 50, 256), (1, 70, 4096), (2, 33, 1000 if quant_bits else 130), (1, 5, 2048), (1, 9, 6152),
+              (1, 3, 10240)]      # the last one is too long a row to share a quantised launch
+    hp = mlc.OuterHParams(K=K, eta_out=0.9, mu=0.8, quant_bits=quant_bits, error_feedback=ef, ef_beta=0.9)
+
+    def build():
+        groups = []
+        for gi, (cnt, m, n) in enumerate(shapes):
+            tg0, ws0, u0 = _inputs(cnt, m, n, K, torch.bfloat16, torch.float32, seed=100 + gi)
+            g = mlc.OuterGroup([w.to(DEV) for w in ws0], tg0.to(DEV), u0.to(DEV))
+            if quant_bits:
+                g.codes = [torch.full((cnt * m, n * quant_bits // 8), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(K)]
+                g.scales = [torch.full((cnt * m,), -1.0, dtype=torch.float32, device=DEV) for _ in range(K)]
+            if ef:
+                g.residuals = [S.normal((cnt, m, n), 1e-3, 100 + gi, 50 + k).to(DEV) for k in range(K)]
+            groups.append(g)
+        return groups
+
+    together, apart = build(), build()
+    mlc.muloco_outer_step(together, hp)              # six groups: one launch of four, then single ones
+    for g in apart:
+        mlc.muloco_outer_step([g], hp)
+    torch.cuda.synchronize()
+    for a, b in zip(together, apart):
+        assert torch.equal(a.global_param, b.global_param) and torch.equal(a.outer_momentum, b.outer_momentum)
+        for k in range(K):
+            assert torch.equal(a.worker_params[k].view(torch.int16), b.worker_params[k].view(torch.int16))
+            if quant_bits:
+                assert torch.equal(a.codes[k], b.codes[k])
+                assert torch.equal(a.scales[k].view(torch.int32), b.scales[k].view(torch.int32))
+            if ef:
+                assert torch.equal(a.residuals[k].view(torch.int32), b.residuals[k].view(torch.int32))
