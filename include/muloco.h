@@ -131,7 +131,10 @@ typedef struct {
   float ns_eps;          /* added to the Frobenius norm (1e-7)                         */
 } mlc_muon_hparams;
 
-/* Work space that lets every group run as a single batch (the largest group decides). */
+/* Work space that holds every group at once, each as a single batch (the sum over groups).
+ * With it the groups go through Newton-Schulz side by side and products of equal depth share
+ * launches; with less (down to the minimum below) the groups are processed one after the
+ * other, in chunks that fit.  The results are the same bit for bit. */
 size_t muloco_inner_workspace_bytes(const mlc_inner_group* groups, int n_groups);
 /* Smallest accepted work space (every group processed one matrix at a time). */
 size_t muloco_inner_workspace_min_bytes(const mlc_inner_group* groups, int n_groups);

@@ -128,77 +128,116 @@ int64_t chunk_for(const NsPlan& p, size_t ws_bytes, int64_t count) {
   return c;
 }
 
-// The `iters` Newton-Schulz iterations on a chunk whose (unnormalised) input sits in X[0]
-// and whose per-matrix partial sums of squares sit in `partials`.  Returns the index of the
-// buffer that holds the result; with iters == 0 the result is X[0] still unscaled, and its
-// factor 1/(norm+eps) sits in `scale`.
+// One batch of same-shape matrices on its way through Newton-Schulz: its (unnormalised) input
+// sits in w.X[0], the per-matrix partial sums of squares in w.partials.
+struct NsJob { NsPlan p; NsBuffers w; int64_t chunk; int result_buf; };
+constexpr int MAX_NS_JOBS = 16;
+
+// The three products of one iteration of job j (X = current buffer, Xn = the other one).
 //
 // The polynomial is folded before the last product: B' = a I + b A + c A^2, X <- B' X,
 // which is the printed iteration with one rounding to bf16 fewer.  The normalisation is
 // folded into the first iteration's scalars: A_0 = s^2 U U^T, X_1 = s B' U.
-int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
-                 float c, float eps, hipStream_t stream, int* result_buf) {
+static GemmDesc gram_desc(const NsJob& j, const bf16_t* X, bool first) {
+  const NsPlan& p = j.p;
   const bool wide = p.mp <= p.np;
   const int64_t xs = p.mp * p.ldx, ss = p.sp * p.lds;
-  if (iters >= 1 && ns_chain_small_fits(p.mp, p.np)) {
-    // small matrices: norm and all iterations in one launch, X and A resident in LDS
-    *result_buf = 1;
-    return launch_ns_chain_small(w.X[0], w.X[1], p.ldx, xs, p.mp, p.np, w.partials, p.nblk, eps, chunk,
-                                 iters, a, b, c, stream);
+  GemmDesc g{};
+  // Gram matrix: A = X X^T (wide) or X^T X (tall)
+  g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = wide ? 0 : 1;
+  g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = wide ? 0 : 1;
+  g.D = j.w.A; g.ldd = p.lds; g.strideD = ss;
+  g.C = nullptr;
+  g.M = (int)p.sp; g.N = (int)p.sp; g.K = (int)(wide ? p.np : p.mp); g.batch = (int)j.chunk;
+  g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
+  g.bscale = first ? j.w.scale : nullptr; g.bscale_pow = 2;
+  g.symmetric = 1;     // only the lower triangle of tiles is computed, then mirrored
+  return g;
+}
+static GemmDesc poly_desc(const NsJob& j, float a, float b, float c) {
+  const NsPlan& p = j.p;
+  const int64_t ss = p.sp * p.lds;
+  // Polynomial: B' = c A A + b A + a I.  A is symmetric, so either operand may be read
+  // along rows or along columns; the K-contiguous LDS path is the faster one.
+  GemmDesc g{};
+  g.A = j.w.A; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
+  g.B = j.w.A; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
+  g.D = j.w.B; g.ldd = p.lds; g.strideD = ss;
+  g.C = j.w.A; g.ldc = p.lds; g.strideC = ss;
+  g.M = g.N = g.K = (int)p.sp; g.batch = (int)j.chunk;
+  g.alpha = c; g.beta = b; g.gamma = a;
+  g.symmetric = 1;
+  return g;
+}
+static GemmDesc apply_desc(const NsJob& j, const bf16_t* X, bf16_t* Xn, bool first) {
+  const NsPlan& p = j.p;
+  const bool wide = p.mp <= p.np;
+  const int64_t xs = p.mp * p.ldx, ss = p.sp * p.lds;
+  // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
+  GemmDesc g{};
+  if (wide) {     // B' symmetric: read along rows (K-contiguous); X has k as its slow index
+    g.A = j.w.B; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
+    g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = 1;
+    g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
+  } else {
+    g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = 0;
+    g.B = j.w.B; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
+    g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.np;
   }
-  {
-    const int rc = launch_norm_finalize(w.partials, p.nblk, w.scale, chunk, eps, stream);
-    if (rc != MLC_OK) return rc;
-  }
-  int cur = 0;
-  for (int it = 0; it < iters; ++it) {
-    const bf16_t* X = w.X[cur];
-    bf16_t* Xn = w.X[cur ^ 1];
-    GemmDesc g{};
-    // Gram matrix: A = X X^T (wide) or X^T X (tall)
-    g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = wide ? 0 : 1;
-    g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = wide ? 0 : 1;
-    g.D = w.A; g.ldd = p.lds; g.strideD = ss;
-    g.C = nullptr;
-    g.M = (int)p.sp; g.N = (int)p.sp; g.K = (int)(wide ? p.np : p.mp); g.batch = (int)chunk;
-    g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
-    g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 2;
-    g.symmetric = 1;     // only the lower triangle of tiles is computed, then mirrored
-    int rc = launch_ns_gemm(g, stream);
-    if (rc != MLC_OK) return rc;
-    // Polynomial: B' = c A A + b A + a I.  A is symmetric, so either operand may be read
-    // along rows or along columns; the K-contiguous LDS path is the faster one.
-    g = GemmDesc{};
-    g.A = w.A; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
-    g.B = w.A; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
-    g.D = w.B; g.ldd = p.lds; g.strideD = ss;
-    g.C = w.A; g.ldc = p.lds; g.strideC = ss;
-    g.M = g.N = g.K = (int)p.sp; g.batch = (int)chunk;
-    g.alpha = c; g.beta = b; g.gamma = a;
-    g.symmetric = 1;
-    rc = launch_ns_gemm(g, stream);
-    if (rc != MLC_OK) return rc;
-    // Apply: X <- B' X (wide) or X B' (tall; B' symmetric)
-    g = GemmDesc{};
-    if (wide) {     // B' symmetric: read along rows (K-contiguous); X has k as its slow index
-      g.A = w.B; g.lda = p.lds; g.strideA = ss; g.a_kstrided = 0;
-      g.B = X; g.ldb = p.ldx; g.strideB = xs; g.b_kstrided = 1;
-      g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.mp;
-    } else {
-      g.A = X; g.lda = p.ldx; g.strideA = xs; g.a_kstrided = 0;
-      g.B = w.B; g.ldb = p.lds; g.strideB = ss; g.b_kstrided = 0;
-      g.M = (int)p.mp; g.N = (int)p.np; g.K = (int)p.np;
+  g.D = Xn; g.ldd = p.ldx; g.strideD = xs;
+  g.C = nullptr; g.batch = (int)j.chunk;
+  g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
+  g.bscale = first ? j.w.scale : nullptr; g.bscale_pow = 1;
+  return g;
+}
+
+// The `iters` Newton-Schulz iterations on n independent jobs.  On return result_buf of a job
+// is the index of the buffer that holds its result; with iters == 0 the result is X[0] still
+// unscaled, and its factor 1/(norm+eps) sits in `scale`.  The same product of several jobs
+// goes out as one set, so that products of equal depth can share launches.
+int run_ns_jobs(NsJob* jobs, int n, int iters, float a, float b, float c, float eps, hipStream_t stream) {
+  if (n < 1 || n > MAX_NS_JOBS) return MLC_ERR_ARG;
+  NsJob* big[MAX_NS_JOBS];
+  int nbig = 0;
+  for (int i = 0; i < n; ++i) {
+    NsJob& j = jobs[i];
+    if (iters >= 1 && ns_chain_small_fits(j.p.mp, j.p.np)) {
+      // small matrices: norm and all iterations in one launch, X and A resident in LDS
+      j.result_buf = 1;
+      const int rc = launch_ns_chain_small(j.w.X[0], j.w.X[1], j.p.ldx, j.p.mp * j.p.ldx, j.p.mp, j.p.np,
+                                           j.w.partials, j.p.nblk, eps, j.chunk, iters, a, b, c, stream);
+      if (rc != MLC_OK) return rc;
+      continue;
     }
-    g.D = Xn; g.ldd = p.ldx; g.strideD = xs;
-    g.C = nullptr; g.batch = (int)chunk;
-    g.alpha = 1.f; g.beta = 0.f; g.gamma = 0.f;
-    g.bscale = it == 0 ? w.scale : nullptr; g.bscale_pow = 1;
-    rc = launch_ns_gemm(g, stream);
+    const int rc = launch_norm_finalize(j.w.partials, j.p.nblk, j.w.scale, j.chunk, eps, stream);
+    if (rc != MLC_OK) return rc;
+    j.result_buf = 0;
+    big[nbig++] = &j;
+  }
+  GemmDesc d[MAX_NS_JOBS];
+  int cur = 0;
+  for (int it = 0; it < iters && nbig > 0; ++it) {
+    for (int i = 0; i < nbig; ++i) d[i] = gram_desc(*big[i], big[i]->w.X[cur], it == 0);
+    int rc = launch_ns_gemm_set(d, nbig, stream);
+    if (rc != MLC_OK) return rc;
+    for (int i = 0; i < nbig; ++i) d[i] = poly_desc(*big[i], a, b, c);
+    rc = launch_ns_gemm_set(d, nbig, stream);
+    if (rc != MLC_OK) return rc;
+    for (int i = 0; i < nbig; ++i) d[i] = apply_desc(*big[i], big[i]->w.X[cur], big[i]->w.X[cur ^ 1], it == 0);
+    rc = launch_ns_gemm_set(d, nbig, stream);
     if (rc != MLC_OK) return rc;
     cur ^= 1;
   }
-  *result_buf = cur;
+  for (int i = 0; i < nbig; ++i) big[i]->result_buf = cur;
   return MLC_OK;
+}
+
+int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
+                 float c, float eps, hipStream_t stream, int* result_buf) {
+  NsJob j{p, w, chunk, 0};
+  const int rc = run_ns_jobs(&j, 1, iters, a, b, c, eps, stream);
+  *result_buf = j.result_buf;
+  return rc;
 }
 
 int check_workspace(const void* ws, size_t bytes, size_t need) {
@@ -335,8 +374,21 @@ static int check_inner_groups(const mlc_inner_group* groups, int n_groups) {
   return MLC_OK;
 }
 
+// Work space with which all groups are resident at once, each as a single batch: the sum over
+// groups (0 when a group is too large to be one batch).
+static size_t inner_workspace_all(const mlc_inner_group* groups, int n_groups) {
+  size_t need = 0;
+  for (int i = 0; i < n_groups; ++i) {
+    if (groups[i].count > MAX_CHUNK) return 0;
+    need += make_plan(groups[i].m, groups[i].n).per_matrix * (size_t)groups[i].count;
+  }
+  return need;
+}
+
 size_t muloco_inner_workspace_bytes(const mlc_inner_group* groups, int n_groups) {
   if (check_inner_groups(groups, n_groups) != MLC_OK) return 0;
+  const size_t all = (n_groups <= MAX_NS_JOBS) ? inner_workspace_all(groups, n_groups) : 0;
+  if (all) return all;
   size_t need = 0;
   for (int i = 0; i < n_groups; ++i) {
     const size_t b = newton_schulz_workspace_bytes(groups[i].count, groups[i].m, groups[i].n);
@@ -366,6 +418,37 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
   if (rc != MLC_OK) return rc;
   hipStream_t stream = (hipStream_t)stream_;
   const float decay_factor = 1.0f - hp->eta * hp->weight_decay;
+  // With room for every group at once the groups go through Newton-Schulz side by side, so that
+  // their products of equal depth share launches; otherwise one group after the other, in
+  // chunks that fit.  Both give the same bits.
+  const size_t all = (n_groups >= 2 && n_groups <= MAX_NS_JOBS) ? inner_workspace_all(groups, n_groups) : 0;
+  if (all && workspace_bytes >= all) {
+    NsJob jobs[MAX_NS_JOBS];
+    unsigned char* base = (unsigned char*)workspace;
+    for (int gi = 0; gi < n_groups; ++gi) {
+      const mlc_inner_group& g = groups[gi];
+      jobs[gi].p = make_plan(g.m, g.n);
+      jobs[gi].chunk = g.count;
+      jobs[gi].w = carve(jobs[gi].p, base, g.count);
+      jobs[gi].result_buf = 0;
+      base += jobs[gi].p.per_matrix * (size_t)g.count;
+      rc = launch_momentum(g.grad, g.grad_dtype, g.momentum, jobs[gi].w.X[0], jobs[gi].w.partials,
+                           jobs[gi].p.nblk, g.count, g.m, g.n, jobs[gi].p.mp, jobs[gi].p.np, jobs[gi].p.ldx,
+                           hp->beta, hp->nesterov, stream);
+      if (rc != MLC_OK) return rc;
+    }
+    rc = run_ns_jobs(jobs, n_groups, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, hp->ns_eps, stream);
+    if (rc != MLC_OK) return rc;
+    for (int gi = 0; gi < n_groups; ++gi) {
+      const mlc_inner_group& g = groups[gi];
+      const NsJob& j = jobs[gi];
+      rc = launch_param_update(g.param, g.param_dtype, j.w.X[j.result_buf],
+                               hp->ns_iters == 0 ? j.w.scale : nullptr, g.count, g.m, g.n, j.p.mp, j.p.ldx,
+                               decay_factor, hp->eta * g.lr_scale, stream);
+      if (rc != MLC_OK) return rc;
+    }
+    return MLC_OK;
+  }
   for (int gi = 0; gi < n_groups; ++gi) {
     const mlc_inner_group& g = groups[gi];
     const NsPlan p = make_plan(g.m, g.n);

@@ -85,6 +85,10 @@ struct GemmDesc {
                          // tiles and store each off-diagonal tile twice
 };
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream);
+// n independent products (n <= 64).  Those of equal depth K that use the large tile and the
+// same kind of epilogue share launches, up to three at a time; each result is what
+// launch_ns_gemm gives for that product, bit for bit.
+int launch_ns_gemm_set(const GemmDesc* d, int n, hipStream_t stream);
 
 // ---- whole Newton-Schulz chain of a small matrix in one workgroup (ns_chain_small.hip) ----
 // Fits when the padded short side is 128 and the padded long side at most 512.

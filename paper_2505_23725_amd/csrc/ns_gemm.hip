@@ -47,6 +47,7 @@ constexpr int NPRE = 4;          // K tiles requested when an output tile starts
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;        // most tile rows per group of the tile order
+constexpr long MIN_TILES_256 = 160;   // fewest 256 x 256 tiles of a product for which that tile is used
 
 struct GemmArgs {
   const bf16_t* A; long lda, strideA;
@@ -360,17 +361,14 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
 // Workgroups are dealt round-robin to the 8 XCDs, so XCD x owns the contiguous range of
 // tiles [x * tiles_per_xcd, (x + 1) * tiles_per_xcd) and its workgroups take them in
 // order: tiles that share operand panels run at the same time behind the same L2.
+// The tiles logical, logical + g.wg_per_xcd, ... below range_end of one product, by one workgroup.
 template <int BM, int BN, bool AKS, bool BKS>
-__global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
+__device__ __forceinline__ void run_tiles(const GemmArgs& g, int logical, const int range_end) {
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const unsigned int lds0 =
       (unsigned int)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem;
-
-  const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
-  const int range_end = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
-  int logical = xcd * g.tiles_per_xcd + slot;
   if (logical >= range_end) return;
 
   auto decode = [&](int t) {
@@ -600,6 +598,51 @@ __global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
   }
 }
 
+template <int BM, int BN, bool AKS, bool BKS>
+__global__ __launch_bounds__(NTHREADS) void ns_gemm_bf16_kernel(GemmArgs g) {
+  const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
+  const int range_end = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
+  run_tiles<BM, BN, AKS, BKS>(g, xcd * g.tiles_per_xcd + slot, range_end);
+}
+
+// Several products of equal depth K in one launch (the same product of a Newton-Schulz
+// iteration for several shape groups).  A launch whose tile count is not a multiple of the
+// number of compute units pays for a partly empty last round; sharing a launch leaves one
+// such round instead of one per group.  XCD x still owns a contiguous range of every
+// product's tile order; inside it the workgroups take the products one after the other, each
+// starting with the workgroup after the one that took the previous product's last tile, so
+// that no workgroup ends up with more than one tile over the average.  LAYOUTS: bit 0 =
+// both operands K-contiguous, bit 1 = both K-strided, bit 2 = A K-contiguous and B
+// K-strided; only the listed tile loops are compiled in.
+constexpr int MAX_MULTI = 3;
+enum { LAYOUT_KC_KC = 0, LAYOUT_KS_KS = 1, LAYOUT_KC_KS = 2 };
+struct MultiArgs { GemmArgs seg[MAX_MULTI]; int layout[MAX_MULTI]; int nseg; };
+
+template <int BM, int BN, int LAYOUTS>
+__global__ __launch_bounds__(NTHREADS) void ns_gemm_multi_kernel(MultiArgs m) {
+  const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
+  const int W = (int)(gridDim.x / NUM_XCD);
+  int off = 0;         // workgroups of this XCD that already received a tile more than the others
+#pragma unroll 1
+  for (int j = 0; j < m.nseg; ++j) {
+    const GemmArgs& g = m.seg[j];
+    const int lo = min(xcd * g.tiles_per_xcd, g.total_tiles);
+    const int hi = min((xcd + 1) * g.tiles_per_xcd, g.total_tiles);
+    int pos = slot - off;
+    if (pos < 0) pos += W;
+    const int first = lo + pos;
+    const int lay = m.layout[j];
+    if (first < hi) {
+      if ((LAYOUTS & 1) && lay == LAYOUT_KC_KC) run_tiles<BM, BN, false, false>(g, first, hi);
+      if ((LAYOUTS & 2) && lay == LAYOUT_KS_KS) run_tiles<BM, BN, true, true>(g, first, hi);
+      if ((LAYOUTS & 4) && lay == LAYOUT_KC_KS) run_tiles<BM, BN, false, true>(g, first, hi);
+    }
+    off = (off + (hi - lo)) % W;
+    // the next product's first transfers overwrite the ring: every wavefront must have left it
+    __syncthreads();
+  }
+}
+
 // Compute units behind one L2 (one XCD) of the current device.
 int cus_per_xcd(int slot) {
   static std::atomic<int> cached[MAX_DEVICES];
@@ -615,9 +658,16 @@ int cus_per_xcd(int slot) {
   return cus / NUM_XCD;
 }
 
-template <int BM, int BN, bool AKS, bool BKS>
-int launch_cfg(const GemmDesc& d, hipStream_t stream) {
-  GemmArgs g;
+// Dynamic LDS a kernel asks for: its ring, and at least 96 KiB so that no second workgroup
+// fits beside it on a CU.
+template <int BM, int BN>
+constexpr size_t exclusive_lds_bytes() {
+  return (size_t)NSTAGE * (BM + BN) * BK * 2 > 96 * 1024 ? (size_t)NSTAGE * (BM + BN) * BK * 2 : (size_t)96 * 1024;
+}
+
+// Kernel arguments of one product with BM x BN tiles; wg_per_xcd is left to the caller.
+template <int BM, int BN>
+int make_args(const GemmDesc& d, GemmArgs& g) {
   g.A = d.A; g.lda = d.lda; g.strideA = d.strideA;
   g.B = d.B; g.ldb = d.ldb; g.strideB = d.strideB;
   g.D = d.D; g.ldd = d.ldd; g.strideD = d.strideD;
@@ -635,27 +685,87 @@ int launch_cfg(const GemmDesc& d, hipStream_t stream) {
   if (total <= 0 || total > (1L << 30)) return MLC_ERR_SHAPE;
   g.total_tiles = (int)total;
   g.tiles_per_xcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
-  // one workgroup per CU for the 256 x 256 tile (its ring fills the 160 KiB of LDS), two for 128 x 128
-  const int per_cu = (BM == 256) ? 1 : 2;
-  const int slot = device_slot();
-  g.wg_per_xcd = cus_per_xcd(slot) * per_cu;
-  if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
+  g.wg_per_xcd = 0;
   g.alpha = d.alpha; g.beta = d.beta; g.gamma = d.gamma;
   g.bscale = d.bscale; g.bscale_pow = d.bscale_pow;
-  const size_t lds = (size_t)NSTAGE * (BM + BN) * BK * 2;
-  auto kern = ns_gemm_bf16_kernel<BM, BN, AKS, BKS>;
-  // The LDS limit of a kernel is raised once per instantiation and device (the call is
-  // idempotent, so a race between two host threads only repeats it).
-  static std::atomic<bool> attr_set[MAX_DEVICES];
-  if (slot < 0 || !attr_set[slot].load(std::memory_order_acquire)) {
+  return MLC_OK;
+}
+
+// The LDS limit of a kernel is raised once per instantiation and device (the call is
+// idempotent, so a race between two host threads only repeats it).
+template <typename Kern>
+int raise_lds_limit(Kern kern, std::atomic<bool>* done, int slot, size_t lds) {
+  if (slot < 0 || !done[slot].load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return MLC_ERR_LAUNCH;
-    if (slot >= 0) attr_set[slot].store(true, std::memory_order_release);
+    if (slot >= 0) done[slot].store(true, std::memory_order_release);
   }
-  const double flops = 2.0 * BM * BN * (double)d.K * (double)total;   // executed, not nominal
+  return MLC_OK;
+}
+
+template <int BM, int BN, bool AKS, bool BKS>
+int launch_cfg(const GemmDesc& d, hipStream_t stream) {
+  GemmArgs g;
+  int rc = make_args<BM, BN>(d, g);
+  if (rc != MLC_OK) return rc;
+  // One workgroup per CU.  The ring of the 256 x 256 tile fills the 160 KiB of LDS anyway; the
+  // 128 x 128 tile's ring is 80 KiB and two such workgroups would fit, but with two of them
+  // on one CU the tiles of the second one came out wrong (garbage, from run to run on
+  // different tiles), so the kernel asks for more than half of the LDS and a CU never holds
+  // two.  (Suspected, not established: the LDS address of `buffer_load ... lds`, taken from
+  // m0, when the workgroup's LDS allocation does not start at 0.)
+  const int slot = device_slot();
+  g.wg_per_xcd = cus_per_xcd(slot);
+  if (g.wg_per_xcd > g.tiles_per_xcd) g.wg_per_xcd = g.tiles_per_xcd;
+  const size_t lds = exclusive_lds_bytes<BM, BN>();
+  auto kern = ns_gemm_bf16_kernel<BM, BN, AKS, BKS>;
+  static std::atomic<bool> attr_set[MAX_DEVICES];
+  rc = raise_lds_limit(kern, attr_set, slot, lds);
+  if (rc != MLC_OK) return rc;
+  const double flops = 2.0 * BM * BN * (double)d.K * (double)g.total_tiles;   // executed, not nominal
   LaunchScope scope(MLC_KERNEL_NS_GEMM, stream, flops, 0.0);
   hipLaunchKernelGGL(kern, dim3(g.wg_per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, g);
+  return hipGetLastError() == hipSuccess ? MLC_OK : MLC_ERR_LAUNCH;
+}
+
+int layout_of(const GemmDesc& d) {
+  if (!d.a_kstrided && !d.b_kstrided) return LAYOUT_KC_KC;
+  if (d.a_kstrided && d.b_kstrided) return LAYOUT_KS_KS;
+  if (!d.a_kstrided && d.b_kstrided) return LAYOUT_KC_KS;
+  return -1;
+}
+
+bool valid_desc(const GemmDesc& d) {
+  if (d.M % 128 || d.N % 128 || d.K % 128 || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0) return false;
+  if ((d.lda | d.ldb | d.ldd | d.strideA | d.strideB | d.strideD) % 8) return false;
+  if (d.C && ((d.ldc | d.strideC) % 8)) return false;
+  return true;
+}
+
+// n (2 or 3) products of one depth K with 256 x 256 tiles in one launch.
+template <int LAYOUTS>
+int launch_multi(const GemmDesc* const* d, int n, hipStream_t stream) {
+  MultiArgs m;
+  m.nseg = n;
+  const int slot = device_slot();
+  const int W = cus_per_xcd(slot);
+  double flops = 0.0;
+  for (int j = 0; j < MAX_MULTI; ++j) {
+    const GemmDesc& dj = *d[j < n ? j : 0];
+    const int rc = make_args<256, 256>(dj, m.seg[j]);
+    if (rc != MLC_OK) return rc;
+    m.seg[j].wg_per_xcd = W;
+    m.layout[j] = layout_of(dj);
+    if (j < n) flops += 2.0 * 256 * 256 * (double)dj.K * (double)m.seg[j].total_tiles;
+  }
+  const size_t lds = exclusive_lds_bytes<256, 256>();
+  auto kern = ns_gemm_multi_kernel<256, 256, LAYOUTS>;
+  static std::atomic<bool> attr_set[MAX_DEVICES];
+  const int rc = raise_lds_limit(kern, attr_set, slot, lds);
+  if (rc != MLC_OK) return rc;
+  LaunchScope scope(MLC_KERNEL_NS_GEMM, stream, flops, 0.0);
+  hipLaunchKernelGGL(kern, dim3(W * NUM_XCD), dim3(NTHREADS), lds, stream, m);
   return hipGetLastError() == hipSuccess ? MLC_OK : MLC_ERR_LAUNCH;
 }
 
@@ -672,13 +782,55 @@ int launch_layout(const GemmDesc& d, hipStream_t stream) {
 }  // namespace
 
 int launch_ns_gemm(const GemmDesc& d, hipStream_t stream) {
-  if (d.M % 128 || d.N % 128 || d.K % 128 || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.batch <= 0)
-    return MLC_ERR_SHAPE;
-  if ((d.lda | d.ldb | d.ldd | d.strideA | d.strideB | d.strideD) % 8) return MLC_ERR_SHAPE;
-  if (d.C && ((d.ldc | d.strideC) % 8)) return MLC_ERR_SHAPE;
+  if (!valid_desc(d)) return MLC_ERR_SHAPE;
+  // The large tile as soon as it occupies most of the chip for one round: the small tile moves
+  // twice the operand bytes per FLOP and needs four times the tiles.
   const long tiles256 = (long)(d.M / 256) * (d.N / 256) * d.batch;
-  if (d.M % 256 == 0 && d.N % 256 == 0 && tiles256 >= 256) return launch_layout<256, 256>(d, stream);
+  if (d.M % 256 == 0 && d.N % 256 == 0 && tiles256 >= MIN_TILES_256) return launch_layout<256, 256>(d, stream);
   return launch_layout<128, 128>(d, stream);
+}
+
+int launch_ns_gemm_set(const GemmDesc* d, int n, hipStream_t stream) {
+  if (n < 0 || n > 64) return MLC_ERR_ARG;
+  bool done[64] = {};
+  for (int i = 0; i < n; ++i) {
+    if (done[i]) continue;
+    if (!valid_desc(d[i])) return MLC_ERR_SHAPE;
+    // products that can share a launch with product i: same depth (a tile then takes the same
+    // time in each, so dealing tiles out evenly balances the time), 256 x 256 tiles, the same
+    // kind of epilogue, and a combination of operand layouts one of the kernels holds
+    const GemmDesc* pick[MAX_MULTI] = {&d[i], nullptr, nullptr};
+    int idx[MAX_MULTI] = {i, -1, -1};
+    int np = 1, layouts = 1 << (layout_of(d[i]) < 0 ? 0 : layout_of(d[i]));
+    const bool tile256 = d[i].M % 256 == 0 && d[i].N % 256 == 0 && layout_of(d[i]) >= 0;
+    long tiles = tile256 ? (long)(d[i].M / 256) * (d[i].N / 256) * d[i].batch : 0;
+    for (int j = i + 1; tile256 && j < n && np < MAX_MULTI; ++j) {
+      if (done[j] || !valid_desc(d[j]) || layout_of(d[j]) < 0) continue;
+      if (d[j].K != d[i].K || d[j].M % 256 || d[j].N % 256 || (d[j].symmetric != 0) != (d[i].symmetric != 0) ||
+          (d[j].C != nullptr) != (d[i].C != nullptr))
+        continue;
+      const int both = layouts | (1 << layout_of(d[j]));
+      if (both != 1 && both != 3 && both != 4 && both != 5) continue;      // the combinations that are built
+      layouts = both;
+      pick[np] = &d[j];
+      idx[np] = j;
+      tiles += (long)(d[j].M / 256) * (d[j].N / 256) * d[j].batch;
+      ++np;
+    }
+    int rc;
+    if (np >= 2 && tiles >= MIN_TILES_256) {
+      if (layouts == 1) rc = launch_multi<1>(pick, np, stream);
+      else if (layouts == 3) rc = launch_multi<3>(pick, np, stream);
+      else rc = launch_multi<5>(pick, np, stream);      // also serves two products with layout bit 2 alone
+      if (rc != MLC_OK) return rc;
+      for (int k = 0; k < np; ++k) done[idx[k]] = true;
+      continue;
+    }
+    rc = launch_ns_gemm(d[i], stream);
+    if (rc != MLC_OK) return rc;
+    done[i] = true;
+  }
+  return MLC_OK;
 }
 
 }  // namespace mlc

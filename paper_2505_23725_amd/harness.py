@@ -76,7 +76,8 @@ class MulocoJob:
         self.workspace = None
         if outer_only:
             return
-        need = max(B.newton_schulz_workspace_bytes(self.K * s[0], s[1], s[2]) for s in self.shapes)
+        # room for all shape groups at once: their products of equal depth then share launches
+        need = B.muloco_inner_workspace_bytes(self.inner_groups_all())
         floor = max(B.newton_schulz_workspace_min_bytes(s[1], s[2]) for s in self.shapes)
         if workspace_cap_bytes is not None:
             need = max(floor, min(need, workspace_cap_bytes))

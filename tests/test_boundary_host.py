@@ -122,6 +122,15 @@ def test_inner_step_argument_errors():
     assert lib.muloco_inner_step(arr, 0, C.byref(hp), None, 0, None) == 0     # nothing to do
     assert lib.muloco_inner_workspace_bytes(arr, 1) == 2 * mlc.newton_schulz_workspace_min_bytes(128, 256)
     assert lib.muloco_inner_workspace_min_bytes(arr, 1) == mlc.newton_schulz_workspace_min_bytes(128, 256)
+    # several groups: room for all of them at once (they then share launches), not just for the largest
+    arr3 = (B._InnerGroup * 3)(_inner_group(), _inner_group(), _inner_group())
+    arr3[1].count, arr3[1].m, arr3[1].n = 3, 256, 256
+    arr3[2].count, arr3[2].m, arr3[2].n = 1, 512, 128
+    want = (arr3[0].count * mlc.newton_schulz_workspace_min_bytes(arr3[0].m, arr3[0].n)
+            + 3 * mlc.newton_schulz_workspace_min_bytes(256, 256) + mlc.newton_schulz_workspace_min_bytes(512, 128))
+    assert lib.muloco_inner_workspace_bytes(arr3, 3) == want
+    assert lib.muloco_inner_workspace_min_bytes(arr3, 3) == max(
+        mlc.newton_schulz_workspace_min_bytes(a.m, a.n) for a in arr3)
 
 
 def test_outer_step_argument_errors():

@@ -120,3 +120,44 @@ def test_zero_iterations_uses_normalised_direction():
     Wr, mr, _ = _oracle_group(W0, g, m0, hp, 1.0)
     upd = to_f64(grp.param.cpu()) - to_f64(W0)
     assert rel_fro(upd, Wr - to_f64(W0)) <= 4e-3      # bf16 rounding of the direction only
+
+
+@pytest.mark.parametrize("shapes", [
+    # 150M-like proportions, scaled down: the Gram products of the wide and the tall group share a
+    # launch (depth 1024, K-contiguous next to K-strided), all three polynomial products share one,
+    # and the three apply products (depth 256) share one; a shared launch needs 256 tiles in all
+    [(230, 256, 256), (130, 256, 1024), (130, 1024, 256)],
+    # two groups of one shape and a group that runs the small tile: only some products can share
+    [(50, 512, 512), (50, 512, 512), (3, 384, 640)],
+    # a group that takes the one-workgroup chain beside two that do not
+    [(9, 128, 512), (140, 256, 512), (140, 512, 256)],
+])
+def test_groups_side_by_side_give_the_bits_of_one_group_after_the_other(shapes):
+    """With a work space that holds all groups at once, products of equal depth share launches;
+    with the smaller one each group runs alone.  Both must give the same bits, and one group
+    of each call is checked against the oracle."""
+    hp = mlc.MuonHParams(eta=0.05, weight_decay=0.01, beta=0.9)
+
+    def build():
+        out = []
+        for i, (c, m, n) in enumerate(shapes):
+            W0, g, m0 = _make_group(c, m, n, torch.bfloat16, torch.bfloat16, seed=40 + i)
+            out.append((W0, g, m0, mlc.InnerGroup(W0.to(DEV), g.to(DEV), m0.to(DEV), math.sqrt(n / m))))
+        return out
+
+    both, alone = build(), build()
+    groups = [t[3] for t in both]
+    full = mlc.muloco_inner_workspace_bytes(groups)
+    one = max(mlc.newton_schulz_workspace_bytes(c, m, n) for (c, m, n) in shapes)
+    assert full > one
+    ws = torch.empty(full, dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step(groups, hp, ws)
+    mlc.muloco_inner_step([t[3] for t in alone], hp, ws[:one])
+    torch.cuda.synchronize()
+    for a, b in zip(both, alone):
+        assert torch.equal(a[3].param.view(torch.int16), b[3].param.view(torch.int16))
+        assert torch.equal(a[3].momentum.view(torch.int32), b[3].momentum.view(torch.int32))
+    for (W0, g, m0, grp), (c, m, n) in zip(both, shapes):
+        sl = slice(c - 1, c)        # the last matrix of every group
+        _check_group(W0[sl], g[sl], m0[sl], grp.param[sl].cpu(), grp.momentum[sl].cpu(), hp, math.sqrt(n / m),
+                     f"group {m}x{n}")

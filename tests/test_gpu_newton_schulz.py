@@ -112,6 +112,21 @@ def test_zero_matrix_with_eps_zero_stays_zero():
             assert_ns_close(to_f64(o[1]), ref, f"{shape} eps=0 iters={iters}", 4e-3 if iters == 0 else NS_TOL)
 
 
+@pytest.mark.parametrize("cnt,m,n", [(100, 256, 256), (230, 256, 256), (70, 384, 384), (45, 256, 512), (45, 512, 256)])
+def test_more_small_tiles_than_compute_units(cnt, m, n):
+    """Batches whose products run the 128 x 128 tile with more tiles than compute units (a CU must
+    never hold two of these workgroups: the second one's tiles once came out as garbage): every
+    matrix finite, two runs bit-identical, and matrices from the end of the batch, where the
+    workgroups beyond the first 256 work, match the oracle."""
+    x = S.normal((cnt, m, n), S.GRAD_STD, seed=8, stream=cnt + n, dtype=torch.bfloat16)
+    a = _run(x)
+    b = _run(x)
+    assert torch.isfinite(a.float()).all()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for i in (cnt // 8 - 1, cnt // 8, cnt - 1):       # around the end of the first XCD's range, and the last
+        assert_ns_close(to_f64(a[i]), muon.newton_schulz(to_f64(x[i]), 5), f"matrix {i} of {cnt} x {m} x {n}")
+
+
 def test_singular_values_land_in_the_band():
     x = S.normal((1, 256, 512), S.GRAD_STD, seed=5, stream=0, dtype=torch.bfloat16)
     out = _run(x)
