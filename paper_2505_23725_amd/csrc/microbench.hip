@@ -3,7 +3,8 @@
 // random bit patterns (the most switching activity the datapath can see) and with operands
 // drawn like the workload's (bf16 roundings of 1e-3 * N(0, 1); accumulators stay finite):
 // the chip is power-limited, so the sustained rate depends on the data.  Also the HBM
-// bandwidth of a plain 16-byte copy and of a pure read.  Prints one JSON line.
+// bandwidth of a plain 16-byte copy, of a pure read (plain and non-temporal), of a pure write
+// and of an in-place read-modify-write stream.  Prints one JSON line.
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <cstdio>
@@ -58,6 +59,34 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ in,
   if (acc.x == 0x12345) out[0] = acc;
 }
 
+// In-place read-modify-write of one stream (what an optimizer update does), and a pure write.
+__global__ __launch_bounds__(256) void rmw_kernel(u32x4* __restrict__ a, long n) {
+  const long per_blk = (n + gridDim.x - 1) / gridDim.x;
+  const long b0 = (long)blockIdx.x * per_blk, b1 = (b0 + per_blk < n) ? b0 + per_blk : n;
+  for (long i = b0 + threadIdx.x; i < b1; i += 4 * 256) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (i + u * 256 < b1) v[u] = a[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) if (i + u * 256 < b1) { v[u].x += 1; a[i + u * 256] = v[u]; }
+  }
+}
+__global__ __launch_bounds__(256) void write_kernel(u32x4* __restrict__ a, long n) {
+  const long per_blk = (n + gridDim.x - 1) / gridDim.x;
+  const long b0 = (long)blockIdx.x * per_blk, b1 = (b0 + per_blk < n) ? b0 + per_blk : n;
+  for (long i = b0 + threadIdx.x; i < b1; i += 256) a[i] = u32x4{1u, 2u, 3u, (unsigned)i};
+}
+__global__ __launch_bounds__(256) void read_nt_kernel(const u32x4* __restrict__ in, u32x4* __restrict__ out, long n) {
+  const long per_blk = (n + gridDim.x - 1) / gridDim.x;
+  const long b0 = (long)blockIdx.x * per_blk, b1 = (b0 + per_blk < n) ? b0 + per_blk : n;
+  u32x4 acc = {0, 0, 0, 0};
+  for (long i = b0 + threadIdx.x; i + 3 * 256 < b1; i += 4 * 256) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= __builtin_nontemporal_load(in + i + u * 256);
+  }
+  if (acc.x == 0x12345) out[0] = acc;
+}
+
 int main() {
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   float ms = 0.f;
@@ -102,8 +131,25 @@ int main() {
   for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(read_kernel, dim3(16384), dim3(256), 0, 0, a, b, n);
   CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
   read_gbs = 1.0 * bytes / (ms / 5 * 1e-3) * 1e-9;
+  double read_nt_gbs, write_gbs, rmw_gbs;
+  hipLaunchKernelGGL(read_nt_kernel, dim3(8192), dim3(256), 0, 0, a, b, n);
+  CK(hipEventRecord(e0, 0));
+  for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(read_nt_kernel, dim3(8192), dim3(256), 0, 0, a, b, n);
+  CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+  read_nt_gbs = 1.0 * bytes / (ms / 5 * 1e-3) * 1e-9;
+  hipLaunchKernelGGL(write_kernel, dim3(8192), dim3(256), 0, 0, b, n);
+  CK(hipEventRecord(e0, 0));
+  for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(write_kernel, dim3(8192), dim3(256), 0, 0, b, n);
+  CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+  write_gbs = 1.0 * bytes / (ms / 5 * 1e-3) * 1e-9;
+  hipLaunchKernelGGL(rmw_kernel, dim3(8192), dim3(256), 0, 0, a, n);
+  CK(hipEventRecord(e0, 0));
+  for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(rmw_kernel, dim3(8192), dim3(256), 0, 0, a, n);
+  CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+  rmw_gbs = 2.0 * bytes / (ms / 5 * 1e-3) * 1e-9;
   printf("{\"mfma_bf16_tflops_constant_operands\": %.1f, \"mfma_bf16_tflops_random_operands\": %.1f, "
-         "\"mfma_bf16_tflops_gaussian_operands\": %.1f, \"hbm_copy_GBps\": %.0f, \"hbm_read_GBps\": %.0f}\n",
-         tf[0], tf[1], tf[2], copy_gbs, read_gbs);
+         "\"mfma_bf16_tflops_gaussian_operands\": %.1f, \"hbm_copy_GBps\": %.0f, \"hbm_read_GBps\": %.0f, "
+         "\"hbm_read_nontemporal_GBps\": %.0f, \"hbm_write_GBps\": %.0f, \"hbm_rmw_in_place_GBps\": %.0f}\n",
+         tf[0], tf[1], tf[2], copy_gbs, read_gbs, read_nt_gbs, write_gbs, rmw_gbs);
   return 0;
 }
