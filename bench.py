@@ -346,6 +346,35 @@ def main() -> int:
         torch.cuda.empty_cache()
         return fig
 
+    def inner_on(workload_name, reps):
+        """Muon inner step of another workload (all its replicas), outside the timed region."""
+        w2 = S.WORKLOADS[workload_name]
+        j2 = MulocoJob(w2, device="cuda:0", seed=0, generate_on="device")
+        j2.draw_gradients(0)
+        for _ in range(2):
+            j2.inner_step()
+        torch.cuda.synchronize()
+        mlc.muloco_timing_enable(True)
+        mlc.muloco_timing_read()
+        per = []
+        tot = {"ms": 0.0, "flops": 0.0, "launches": 0, "all_ms": 0.0}
+        for _ in range(reps):
+            j2.inner_step()
+            t2 = mlc.muloco_timing_read()
+            g2 = t2["ns_gemm"]
+            per.append(g2["flops"] / (g2["total_ms"] * 1e-3) * 1e-12 if g2["total_ms"] > 0 else 0.0)
+            tot["ms"] += g2["total_ms"]; tot["flops"] += g2["flops"]; tot["launches"] += g2["launches"]
+            tot["all_ms"] += sum(t2[k]["total_ms"] for k in ("ns_gemm", "momentum", "norm", "update"))
+        mlc.muloco_timing_enable(False)
+        tf = tot["flops"] / (tot["ms"] * 1e-3) * 1e-12 if tot["ms"] > 0 else 0.0
+        fig = {"workload": f"{w2.name}-scale, K={w2.K}", "muon_inner_step_ms": tot["all_ms"] / reps,
+               "ns_gemm_ms": tot["ms"] / reps, "ns_gemm_launches": tot["launches"] / reps,
+               "ns_tflops": tf, "frac_mfma": tf / PEAK_BF16_TFLOPS, "ns_tflops_spread": spread(sorted(per))}
+        del j2
+        torch.cuda.empty_cache()
+        return fig
+
+    ns_150m = inner_on("150m", 10) if wl.name != "150m" else None
     outer_k8_150m = outer_on("150m", 0, 10)
     quantised_outer_k4_31b = outer_on("3.1b", 4, 3)
 
@@ -367,6 +396,7 @@ def main() -> int:
         "ns_flop_per_step": gemm["flops"] / args.steps,
         "momentum": fam("momentum"), "update": fam("update"), "outer": fam("outer"),
         "quantize_outer_fused": fam("dequant_outer"),
+        "ns_150m_k8": ns_150m,
         "outer_k8_150m": outer_k8_150m,
         "quantised_outer_k4_3.1b": quantised_outer_k4_31b,
         "step_ms_spread": spread(step_ms),

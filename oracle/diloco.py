@@ -322,3 +322,14 @@ def outer_step(theta_g, u_prev, thetas, *, eta_out, mu, nesterov=True, quant_bit
     theta, u = outer_update(theta_g, u_prev, psi, eta_out, mu, nesterov)
     out.update(theta=theta, u=u, psi=psi)
     return out
+
+
+def streaming_due(t, H, J):
+    """Partitioned communication (Sec. 2 "Partitioned Communication in Streaming DiLoCo"): with the
+    layers split into J subsets and J | H, subset j (1 <= j <= J) is communicated at the inner
+    steps t that are j * H / J modulo H.  Returns that j for inner step t >= 1, or None."""
+    assert H % J == 0
+    for j in range(1, J + 1):
+        if (t - j * H // J) % H == 0:
+            return j
+    return None

@@ -16,6 +16,30 @@ import synth_inputs as S
 from . import binding as B
 
 
+class StreamingSchedule:
+    """Partitioned communication (paper Sec. 2 "Partitioned Communication in Streaming DiLoCo";
+    Sec. 6 "Streaming MuLoCo"): the layers are split into J subsets, J divides the
+    communication interval H, and subset j (1 <= j <= J) takes its outer step at the inner
+    steps t with t = j * H / J modulo H, so every subset is synchronised once per H steps and
+    1 / J of the model at a time.  Subsets are contiguous runs of layers, as equal as L allows."""
+
+    def __init__(self, layers: int, H: int, J: int):
+        if J < 1 or H < 1 or H % J != 0:
+            raise ValueError("the number of subsets J must divide the communication interval H")
+        if J > layers:
+            raise ValueError("more subsets than layers")
+        self.layers, self.H, self.J = layers, H, J
+        bounds = [round(j * layers / J) for j in range(J + 1)]
+        self.subsets = [range(bounds[j], bounds[j + 1]) for j in range(J)]
+
+    def due(self, t: int) -> Optional[int]:
+        """0-based index of the subset synchronised after inner step t (t counts from 1), or None."""
+        every = self.H // self.J
+        if t < 1 or t % every != 0:
+            return None
+        return (t // every - 1) % self.J
+
+
 class MulocoJob:
     def __init__(self, workload: S.Workload, device="cuda:0", seed: int = 0,
                  layers: Optional[int] = None, K: Optional[int] = None,
@@ -169,16 +193,21 @@ class MulocoJob:
         return out
 
     def layer_fragment(self, layer: int, quant: bool = False, ef: bool = False) -> List[B.OuterGroup]:
-        """Outer-step groups covering one transformer layer (4 d x d, one d x f, one f x d):
-        the unit a streaming schedule synchronises at a time."""
+        """Outer-step groups covering one transformer layer (4 d x d, one d x f, one f x d)."""
+        return self.layers_fragment(range(layer, layer + 1), quant, ef)
+
+    def layers_fragment(self, layers: range, quant: bool = False, ef: bool = False) -> List[B.OuterGroup]:
+        """Outer-step groups covering a contiguous run of layers: the unit a streaming schedule
+        synchronises at a time."""
         out = []
+        l0, l1 = layers.start, layers.stop
         for gi, (c, m, n) in enumerate(self.shapes):
             per_layer = 4 if gi == 0 else 1
-            sl = slice(layer * per_layer, (layer + 1) * per_layer)
+            sl = slice(l0 * per_layer, l1 * per_layer)
             ws = [self.workers[k][gi][sl] for k in range(self.K)]
             g = B.OuterGroup(ws, self.theta_g[gi][sl], self.u[gi][sl])
             if quant:
-                rows = slice(layer * per_layer * m, (layer + 1) * per_layer * m)
+                rows = slice(l0 * per_layer * m, l1 * per_layer * m)
                 g.codes = [self.codes[k][gi][rows] for k in range(self.K)]
                 g.scales = [self.scales[k][gi][rows] for k in range(self.K)]
             if ef:
@@ -203,6 +232,23 @@ class MulocoJob:
 
     def outer_step(self, quant_bits: int = 0) -> None:
         B.muloco_outer_step(self.outer_groups(quant=quant_bits != 0), self.outer_hparams(quant_bits))
+
+    def run_streaming(self, schedule: StreamingSchedule, steps: int, quant_bits: int = 0, first_step: int = 1,
+                      draw: bool = True) -> List[tuple]:
+        """`steps` inner steps of every replica with the outer step of the subset that is due
+        after each of them (paper Sec. 2 "Partitioned Communication").  Returns the
+        (inner step, subset) pairs that were synchronised."""
+        hp = self.outer_hparams(quant_bits=quant_bits)
+        done = []
+        for t in range(first_step, first_step + steps):
+            if draw:
+                self.draw_gradients(t - 1)
+            self.inner_step()
+            j = schedule.due(t)
+            if j is not None:
+                B.muloco_outer_step(self.layers_fragment(schedule.subsets[j], quant=quant_bits != 0), hp)
+                done.append((t, j))
+        return done
 
     @staticmethod
     def capture(fn):

@@ -95,3 +95,55 @@ def test_graph_replay_equals_eager_steps():
                 assert torch.equal(eager.codes[k][gi], replayed.codes[k][gi])
                 assert torch.equal(eager.scales[k][gi], replayed.scales[k][gi])
     assert float(scratch[0]) == 3.0
+
+
+def test_streaming_schedule_two_subsets_two_replicas():
+    """Partitioned communication (Sec. 2 "Partitioned Communication in Streaming DiLoCo") on the
+    smallest workload: K = 2 replicas, H = 8, the two layers as J = 2 subsets, so layer 0 takes its
+    outer step after inner step 4 and layer 1 after inner step 8.  The oracle runs the same
+    trajectory in fp64 with its own schedule."""
+    from paper_2505_23725_amd.harness import MulocoJob, StreamingSchedule
+    wl = S.WORKLOADS["tiny"]
+    K, J = 2, 2
+    job = MulocoJob(wl, generate_on="cpu", seed=0, K=K)
+    sch = StreamingSchedule(wl.layers, wl.H, J)
+    done = job.run_streaming(sch, wl.H)
+    torch.cuda.synchronize()
+    assert done == [(t, diloco.streaming_due(t, wl.H, J) - 1) for t in range(1, wl.H + 1)
+                    if diloco.streaming_due(t, wl.H, J)] == [(4, 0), (8, 1)]
+
+    worst = 0.0
+    for gi, (cnt, m, n) in enumerate(job.shapes):
+        per_layer = cnt // wl.layers
+        th0 = to_f64(S.normal((cnt, m, n), S.PARAM_STD, 0, 100 + gi))
+        theta, u = th0.copy(), np.zeros_like(th0)
+        W = [th0.copy() for _ in range(K)]
+        mom = [np.zeros_like(th0) for _ in range(K)]
+        for t in range(1, wl.H + 1):
+            for k in range(K):
+                g = to_f64(S.normal((cnt, m, n), S.GRAD_STD, 0, job.grad_stream(k, t - 1, gi)))
+                for i in range(cnt):
+                    W[k][i], mom[k][i], _ = muon.inner_step(W[k][i], mom[k][i], g[i], eta=wl.eta_in,
+                                                            weight_decay=wl.weight_decay, beta=wl.beta,
+                                                            nesterov=True, lr_scale=job.lr_scale(m, n))
+            j = diloco.streaming_due(t, wl.H, J)
+            if j:      # the layers of subset j: contiguous matrices of this group
+                sl = slice((j - 1) * per_layer, j * per_layer)
+                out = diloco.outer_step(theta[sl].reshape(-1, n), u[sl].reshape(-1, n),
+                                        [W[k][sl].reshape(-1, n) for k in range(K)], eta_out=wl.eta_out, mu=wl.mu)
+                theta[sl] = out["theta"].reshape(theta[sl].shape)
+                u[sl] = out["u"].reshape(u[sl].shape)
+                for k in range(K):
+                    W[k][sl] = theta[sl]
+        for i in range(cnt):
+            err = rel_fro(to_f64(job.theta_g[gi][i].cpu()) - th0[i], theta[i] - th0[i])
+            worst = max(worst, err)
+            assert err <= NS_TOL, f"group {gi} matrix {i}: global displacement error {err:.3e}"
+            assert rel_fro(to_f64(job.u[gi][i].cpu()), u[i]) <= NS_TOL
+            for k in range(K):
+                assert rel_fro(to_f64(job.workers[k][gi][i].cpu()) - th0[i], W[k][i] - th0[i]) <= NS_TOL
+        # the subset synchronised last holds theta_g in every replica, bit for bit
+        last = slice((J - 1) * per_layer, J * per_layer)
+        for k in range(K):
+            assert torch.equal(job.workers[k][gi][last], job.theta_g[gi][last])
+    print(f"streaming tiny workload: worst global displacement error {worst:.3e}")

@@ -159,3 +159,37 @@ def test_quantised_outer_step_uses_dequantised_deltas():
     u = 0.8 * u0 + 0.9 * psi
     assert np.max(np.abs(out["u"] - u)) < 1e-18
     assert np.max(np.abs(out["theta"] - (tg - 0.8 * u - 0.9 * psi))) < 1e-17
+
+
+# ---- partitioned (streaming) communication --------------------------------------------------
+
+def test_streaming_schedule_every_subset_once_per_interval():
+    """Sec. 2 "Partitioned Communication": subset j at multiples j * H / J; the paper's own setting
+    (Sec. 6 "Streaming MuLoCo": H = 30 in thirds) synchronises a partition every 10 steps."""
+    from oracle import diloco
+    due = [(t, diloco.streaming_due(t, 30, 3)) for t in range(1, 61)]
+    assert [(t, j) for t, j in due if j] == [(10, 1), (20, 2), (30, 3), (40, 1), (50, 2), (60, 3)]
+    # J = 1 is plain DiLoCo: everything every H steps
+    assert [t for t in range(1, 25) if diloco.streaming_due(t, 8, 1)] == [8, 16, 24]
+    for H, J in [(8, 2), (8, 4), (12, 3), (30, 5), (6, 6)]:
+        for start in (1, H + 1):
+            seen = [diloco.streaming_due(t, H, J) for t in range(start, start + H)]
+            assert sorted(j for j in seen if j) == list(range(1, J + 1))      # each subset exactly once
+            assert all((j is None) == (t % (H // J) != 0) for t, j in zip(range(start, start + H), seen))
+
+
+def test_harness_schedule_is_the_oracles():
+    """The harness repeats the schedule (it must not import the oracle); both must agree, and its
+    subsets must tile the layers."""
+    from oracle import diloco
+    from paper_2505_23725_amd.harness import StreamingSchedule
+    for L, H, J in [(2, 8, 2), (12, 30, 3), (24, 30, 5), (7, 12, 4), (5, 5, 1)]:
+        sch = StreamingSchedule(L, H, J)
+        assert [l for r in sch.subsets for l in r] == list(range(L))
+        assert max(len(r) for r in sch.subsets) - min(len(r) for r in sch.subsets) <= 1
+        for t in range(1, 3 * H + 1):
+            j = diloco.streaming_due(t, H, J)
+            assert sch.due(t) == (None if j is None else j - 1)
+    import pytest
+    with pytest.raises(ValueError):
+        StreamingSchedule(12, 30, 4)
