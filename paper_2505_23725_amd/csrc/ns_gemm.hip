@@ -12,8 +12,10 @@
 // line fill the first one started, which halves the requests the L2 has to serve.  A pair
 // is requested as soon as both of its stages are free, two to three K tiles ahead of its
 // use; with five stages that is as far ahead as a four-stage ring of single tiles.  The
-// first four K tiles of the next output tile are requested before the current tile's
-// epilogue.  The compiler does not model these transfers, so their completion is awaited
+// ring does not drain between output tiles: the last two steps of a tile request the first
+// four K tiles of the workgroup's next tile, which are on chip when the epilogue starts, and
+// the next tile's first MFMAs start from zero instead of clearing the accumulators.  The
+// compiler does not model these transfers, so their completion is awaited
 // explicitly (s_waitcnt vmcnt(n): a wavefront's vector-memory loads complete in issue
 // order) before the barrier that publishes a stage.
 //
@@ -242,6 +244,31 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
+// One accumulator element, read where it is needed: the statement keeps the accumulators in
+// their accumulation registers until then (left to itself the compiler copies all of them to
+// ordinary registers first, and from there to scratch memory).
+__device__ __forceinline__ float acc_read(float a) {
+  float x;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(a));
+  return x;
+}
+// The wait states between the last MFMA and the first acc_read of its result (the compiler
+// does not see into either statement); the operands tie the statement to every accumulator.
+template <int TM, int TN>
+__device__ __forceinline__ void acc_settle(const f32x16 (&acc)[TM][TN]) {
+  __builtin_amdgcn_sched_barrier(0);
+  if constexpr (TM == 4)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7"
+                 :: "a"(acc[0][0][15]), "a"(acc[0][1][15]), "a"(acc[0][2][15]), "a"(acc[0][3][15]),
+                    "a"(acc[1][0][15]), "a"(acc[1][1][15]), "a"(acc[1][2][15]), "a"(acc[1][3][15]),
+                    "a"(acc[2][0][15]), "a"(acc[2][1][15]), "a"(acc[2][2][15]), "a"(acc[2][3][15]),
+                    "a"(acc[3][0][15]), "a"(acc[3][1][15]), "a"(acc[3][2][15]), "a"(acc[3][3][15]));
+  else
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7"
+                 :: "a"(acc[0][0][15]), "a"(acc[0][1][15]), "a"(acc[1][0][15]), "a"(acc[1][1][15]));
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // Position of an output tile.
 struct TileCoord { int b, m0, n0; bool mirror; };
 
@@ -283,6 +310,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
       }
   };
   if constexpr (HAS_C) load_c(0);
+  acc_settle(acc);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     // keep the scheduler from pulling the next quarter's accumulator reads up here: all 256
@@ -305,7 +333,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& g, const f32x16 (&acc
         const int roff = TM * (8 * q + rl) + i;           // compile-time row offset
         float v[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) v[j] = alpha * acc[i][j][r];
+        for (int j = 0; j < TN; ++j) v[j] = alpha * acc_read(acc[i][j][r]);
         if constexpr (HAS_C) {
           v[0] += g.beta * bf16lo(cval[rl][i].x);
           v[1] += g.beta * bf16hi(cval[rl][i].x);
@@ -419,10 +447,8 @@ __device__ __forceinline__ void run_tiles(const GemmArgs& g, int logical, const 
   f32x16 acc[TM][TN];
   const int KT = g.K / BK;      // a multiple of 4: K is a multiple of 128
 
-  // Request the first NPRE K tiles of an output tile into stages 0 .. NPRE-1, as pairs.
-  auto start_tile = [&](const TileCoord& tc) {
-    ldA.init(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
-    ldB.init(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
+  // Request the first NPRE K tiles of the first output tile into stages 0 .. NPRE-1, as pairs.
+  auto start_tile = [&]() {
 #pragma unroll
     for (int st = 0; st < NPRE; st += 2) {
 #pragma unroll
@@ -438,14 +464,20 @@ __device__ __forceinline__ void run_tiles(const GemmArgs& g, int logical, const 
     }
   };
 
-  auto mfma_slice = [&](int buf) {
+  auto mfma_slice = [&](int buf, auto zero_tag) {
+    constexpr bool ZERO = decltype(zero_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j) {
+        f32x16 c = acc[i][j];
+        if constexpr (ZERO) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) c[r] = 0.f;
+        }
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]), acc[i][j],
-            0, 0, 0);
+            __builtin_bit_cast(bf16x8, fa[buf][i]), __builtin_bit_cast(bf16x8, fb[buf][j]), c, 0, 0, 0);
+      }
   };
   constexpr int NM = TM * TN;
   constexpr int NDSR = ReaderA::NLOADS + ReaderB::NLOADS;
@@ -465,124 +497,129 @@ __device__ __forceinline__ void run_tiles(const GemmArgs& g, int logical, const 
     if constexpr (TM == 4) { part(I<2>{}); part(I<3>{}); }
   };
   auto nothing = [](int) {};
+  // Workgroup barrier that waits for this wavefront's LDS reads only (a fence would also wait
+  // for every store of the previous tile's epilogue that is still on its way).
+  auto block_sync = []() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-  // Two 32-deep steps on K tiles t (stage r0) and t+1 (stage r1); r2 holds K tile t+2 and r4
-  // is free.  Each step is two 16-deep slices:
+  // The ring never drains between output tiles: a body is two 32-deep steps on K tiles t
+  // (stage r0) and t+1 (stage r1); r2 holds K tile t+2 and r4 is free.  Each step is two
+  // 16-deep slices:
   //   slice 0: MFMAs on fragments 0 | LDS reads of the stage's second slice
   //   wait until the next K tile has landed, barrier: publishes it and retires this stage
   //   slice 1: MFMAs on fragments 1 | LDS reads of the next stage's first slice
-  // REFILL: K tiles t+4 and t+5 are requested into r4 and r0 (r0 is free after the first
-  // barrier).  With a K-contiguous operand the two go as a pair, operand A during slice 1 of
-  // the first step and operand B during slice 0 of the second; when both operands are
-  // K-strided (whole cache lines anyway) they are spread over the four slices instead:
-  // A(t+4), B(t+4), A(t+5), B(t+5).
-  // W1 / W2: transfers that may still be in flight at the first / second barrier, i.e. all
-  // those requested after the K tile the barrier publishes.
-  // LAST: no K tile follows the second step.
+  // Every body requests two K tiles, k4 and k4 + 1 of loader (la, lb), into r4 and r0 (r0 is
+  // free after the first barrier): K tiles t+4 and t+5 of this output tile or, in its last
+  // two bodies, K tiles 0..3 of the workgroup's next output tile, so that tile's first
+  // operands are on chip before this tile's epilogue starts.  With a K-contiguous operand the
+  // two go as a pair, operand A during slice 1 of the first step and operand B during slice 0
+  // of the second; when both operands are K-strided (whole cache lines anyway) they are
+  // spread over the four slices instead: A(k4), B(k4), A(k4+1), B(k4+1).
+  // W1 / W2: vector-memory operations that may still be in flight at the first / second
+  // barrier, i.e. all those issued after the K tile the barrier publishes (they complete in
+  // the order they were issued).  ZERO: the body's first MFMAs start from zero accumulators.
   constexpr bool SPREAD = AKS && BKS;
-  auto body = [&](int t, unsigned int r0, unsigned int r1, unsigned int r2, unsigned int r4,
-                  auto refill_tag, auto w1_tag, auto w2_tag, auto last_tag) {
-    constexpr bool REFILL = decltype(refill_tag)::value, LAST = decltype(last_tag)::value;
+  auto body = [&](const LoaderA& la, const LoaderB& lb, int k4, unsigned int r0, unsigned int r1,
+                  unsigned int r2, unsigned int r4, auto w1_tag, auto w2_tag, auto zero_tag) {
     constexpr int W1 = decltype(w1_tag)::value, W2 = decltype(w2_tag)::value;
     // ---- first step, slice 0
     reads(r0, 1, [&](int p) {
-      if constexpr (REFILL && SPREAD) ldA.issue_one(t + 4, lds0 + r4, p);
+      if constexpr (SPREAD) la.issue_one(k4, lds0 + r4, p);
     });
-    mfma_slice(0);
+    mfma_slice(0, zero_tag);
     rdA.finish(fa[1]); rdB.finish(fb[1]);
     interleave_hint<NM, NDSR, NPERM>();
     // keep slice 0's MFMAs above the barrier: they cover the wait for its LDS reads
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<W1>();
-    __syncthreads();
+    block_sync();
     // ---- first step, slice 1
     reads(r1, 0, [&](int p) {
-      if constexpr (REFILL && SPREAD) ldB.issue_one(t + 4, lds0 + r4 + A_BYTES, p);
-      if constexpr (REFILL && !SPREAD) {
-        ldA.issue_one(t + 4, lds0 + r4, p);
-        ldA.issue_one(t + 5, lds0 + r0, p);
+      if constexpr (SPREAD) lb.issue_one(k4, lds0 + r4 + A_BYTES, p);
+      else {
+        la.issue_one(k4, lds0 + r4, p);
+        la.issue_one(k4 + 1, lds0 + r0, p);
       }
     });
-    mfma_slice(1);
+    mfma_slice(1, std::false_type{});
     rdA.finish(fa[0]); rdB.finish(fb[0]);
     interleave_hint<NM, NDSR, NPERM>();
     // ---- second step, slice 0
     reads(r1, 1, [&](int p) {
-      if constexpr (REFILL && SPREAD) ldA.issue_one(t + 5, lds0 + r0, p);
-      if constexpr (REFILL && !SPREAD) {
-        ldB.issue_one(t + 4, lds0 + r4 + A_BYTES, p);
-        ldB.issue_one(t + 5, lds0 + r0 + A_BYTES, p);
+      if constexpr (SPREAD) la.issue_one(k4 + 1, lds0 + r0, p);
+      else {
+        lb.issue_one(k4, lds0 + r4 + A_BYTES, p);
+        lb.issue_one(k4 + 1, lds0 + r0 + A_BYTES, p);
       }
     });
-    mfma_slice(0);
+    mfma_slice(0, std::false_type{});
     rdA.finish(fa[1]); rdB.finish(fb[1]);
     interleave_hint<NM, NDSR, NPERM>();
-    if constexpr (!LAST) {
-      __builtin_amdgcn_sched_barrier(0);
-      wait_vmcnt<W2>();
-      __syncthreads();
-      reads(r2, 0, [&](int p) {
-        if constexpr (REFILL && SPREAD) ldB.issue_one(t + 5, lds0 + r0 + A_BYTES, p);
-      });
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<W2>();
+    block_sync();
+    reads(r2, 0, [&](int p) {
+      if constexpr (SPREAD) lb.issue_one(k4 + 1, lds0 + r0 + A_BYTES, p);
+    });
     // ---- second step, slice 1
-    mfma_slice(1);
-    if constexpr (!LAST) { rdA.finish(fa[0]); rdB.finish(fb[0]); }
-    interleave_hint<NM, LAST ? 0 : NDSR, LAST ? 0 : NPERM>();
+    mfma_slice(1, std::false_type{});
+    rdA.finish(fa[0]); rdB.finish(fb[0]);
+    interleave_hint<NM, NDSR, NPERM>();
   };
   using T = std::true_type;
   using F = std::false_type;
+  // Operations in flight at a barrier when every body since the K tile it publishes has
+  // requested its two K tiles.  The first three barriers of an output tile publish K tiles
+  // that had landed before the previous tile's epilogue (or before the first tile started):
+  // they wait for nothing (63 is the counter's largest value).
+  constexpr int STEADY = SPREAD ? 2 * NDMA + LoaderA::NCH : 2 * NDMA;
+  constexpr int LANDED = 63;
+
   TileCoord tc = decode(logical);
-  start_tile(tc);
+  ldA.init(g.A + (long)tc.b * g.strideA, g.lda, tc.m0, tid);
+  ldB.init(g.B + (long)tc.b * g.strideB, g.ldb, tc.n0, tid);
+  start_tile();
+  // All four K tiles land before the first body, as they do for every later tile.  Through
+  // the builtin, so that the compiler's own bookkeeping sees every earlier vector-memory
+  // operation as complete.
+  __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0), other counters unconstrained
+  block_sync();
+  reads(0u, 0, nothing);
+  rdA.finish(fa[0]);
+  rdB.finish(fb[0]);
+  // The ring rotates by two stages per body: r[x] = byte offset of the stage that holds
+  // (or will hold) K tile t + x.
+  unsigned int r0 = 0, r1 = STAGE_BYTES, r2 = 2 * STAGE_BYTES, r3 = 3 * STAGE_BYTES, r4 = 4 * STAGE_BYTES;
+  auto rotate = [&]() {
+    const unsigned int a0 = r0, a1 = r1;
+    r0 = r2; r1 = r3; r2 = r4; r3 = a0; r4 = a1;
+  };
   while (true) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // K tile 0 must have landed.  The previous tile's stores are in flight as well, and
-    // stores and loads complete out of order with each other, so wait for everything.
-    // The wait is issued through the builtin so that the compiler's own bookkeeping also
-    // sees every earlier vector-memory operation (spill reloads included) as complete and
-    // inserts no waits of its own inside the K loop.
-    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0), other counters unconstrained
-    __syncthreads();
-    reads(0u, 0, nothing);
-    rdA.finish(fa[0]);
-    rdB.finish(fb[0]);
-
-    // The ring rotates by two stages per body: r[x] = byte offset of the stage that holds
-    // (or will hold) K tile t + x.
-    unsigned int r0 = 0, r1 = STAGE_BYTES, r2 = 2 * STAGE_BYTES, r3 = 3 * STAGE_BYTES, r4 = 4 * STAGE_BYTES;
-    auto rotate = [&]() {
-      const unsigned int a0 = r0, a1 = r1;
-      r0 = r2; r1 = r3; r2 = r4; r3 = a0; r4 = a1;
-    };
-    // Transfers per thread in flight at a barrier of a body whose neighbours all refill,
-    // of the body after the last refill, and of the last body.
-    constexpr int STEADY = SPREAD ? 2 * NDMA + LoaderA::NCH : 2 * NDMA;
-    constexpr int DRAIN1 = 2 * NDMA, DRAIN2 = SPREAD ? NDMA : 0;
-    int t = 0;
-    for (; t + 4 < KT; t += 2) {           // K tiles t+4 and t+5 exist
-      body(t, r0, r1, r2, r4, T{}, I<STEADY>{}, I<STEADY>{}, F{});
-      rotate();
-    }
-    // Last two bodies: nothing left to request, fewer and fewer transfers in flight.
-    body(t, r0, r1, r2, r4, F{}, I<DRAIN1>{}, I<DRAIN2>{}, F{});
-    rotate();
-    body(t + 2, r0, r1, r2, r4, F{}, I<0>{}, I<0>{}, T{});
-
+    // The next output tile of this workgroup; after the last one the same requests go to this
+    // tile's own first K tiles again (in bounds, never read).
     const int next = logical + g.wg_per_xcd;
     const bool more = next < range_end;
-    TileCoord tn = tc;
-    if (more) {
-      // every wavefront must be done reading the ring before it is refilled
-      __syncthreads();
-      tn = decode(next);
-      start_tile(tn);
-    }
+    const TileCoord tn = more ? decode(next) : tc;
+    LoaderA nxA;
+    LoaderB nxB;
+    nxA.init(g.A + (long)tn.b * g.strideA, g.lda, tn.m0, tid);
+    nxB.init(g.B + (long)tn.b * g.strideB, g.ldb, tn.n0, tid);
+    auto run = [&](int t, auto w1_tag, auto w2_tag, auto zero_tag) {
+      const bool tail = t + 4 >= KT;
+      LoaderA la = ldA;
+      LoaderB lb = ldB;
+      if (tail) { la = nxA; lb = nxB; }
+      body(la, lb, tail ? t + 4 - KT : t + 4, r0, r1, r2, r4, w1_tag, w2_tag, zero_tag);
+      rotate();
+    };
+    run(0, I<LANDED>{}, I<LANDED>{}, T{});
+    run(2, I<LANDED>{}, I<STEADY>{}, F{});
+#pragma unroll 1
+    for (int t = 4; t < KT; t += 2) run(t, I<STEADY>{}, I<STEADY>{}, F{});
+
+    // Everything requested so far (the next tile's first four K tiles) lands before the
+    // first store is issued: the waits of the next two bodies then never depend on how
+    // loads and stores complete relative to each other.
+    wait_vmcnt<0>();
     float alpha = g.alpha;
     if (g.bscale) {
       const float sc = g.bscale[tc.b];
@@ -595,7 +632,12 @@ __device__ __forceinline__ void run_tiles(const GemmArgs& g, int logical, const 
     if (!more) break;
     logical = next;
     tc = tn;
+    ldA = nxA;
+    ldB = nxB;
   }
+  // nothing may land in the ring after this workgroup has left it
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  block_sync();
 }
 
 template <int BM, int BN, bool AKS, bool BKS>
