@@ -385,8 +385,12 @@ def main() -> int:
     def fam(name):
         t = timing[name]
         gbs = t["bytes"] / (t["total_ms"] * 1e-3) * 1e-9 if t["total_ms"] > 0 else 0.0
-        return {"ms_per_step": t["total_ms"] / args.steps, "launches_per_step": t["launches"] / args.steps,
-                "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        out = {"ms_per_step": t["total_ms"] / args.steps, "launches_per_step": t["launches"] / args.steps,
+               "GBps": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        if name == "update" and t["launches"] == 0:
+            out = {"ms_per_step": 0.0, "launches_per_step": 0.0,
+                   "note": "bf16 weights: the update is the epilogue of the last Newton-Schulz product"}
+        return out
 
     inner_ms = sum(timing[k]["total_ms"] for k in ("ns_gemm", "momentum", "norm", "update")) / args.steps
     breakdown = {

@@ -130,7 +130,18 @@ int64_t chunk_for(const NsPlan& p, size_t ws_bytes, int64_t count) {
 
 // One batch of same-shape matrices on its way through Newton-Schulz: its (unnormalised) input
 // sits in w.X[0], the per-matrix partial sums of squares in w.partials.
-struct NsJob { NsPlan p; NsBuffers w; int64_t chunk; int result_buf; };
+// With fuse_W set, the last product of the last iteration writes the parameter update itself,
+// W <- fuse_decay * W - fuse_step * O (paper Sec. 2 "Muon"), instead of storing O: O is then
+// never rounded to bf16 nor read back, and result_buf is -1 on return.
+struct NsJob {
+  NsPlan p; NsBuffers w; int64_t chunk; int result_buf;
+  bf16_t* fuse_W = nullptr; float fuse_decay = 0.f, fuse_step = 0.f;
+};
+// The update can ride on the last product when W is bf16 and has the shape the products work
+// on (no padding), and the matrices are not small enough for the one-launch chain.
+static bool can_fuse_update(const NsPlan& p, int param_dtype, int iters) {
+  return iters >= 1 && param_dtype == MLC_BF16 && p.m == p.mp && p.n == p.np && !ns_chain_small_fits(p.mp, p.np);
+}
 constexpr int MAX_NS_JOBS = 16;
 
 // The three products of one iteration of job j (X = current buffer, Xn = the other one).
@@ -190,6 +201,14 @@ static GemmDesc apply_desc(const NsJob& j, const bf16_t* X, bf16_t* Xn, bool fir
   g.bscale = first ? j.w.scale : nullptr; g.bscale_pow = 1;
   return g;
 }
+// The same product with the parameter update as its epilogue: D = decay * W - step * (B' X).
+static GemmDesc apply_update_desc(const NsJob& j, const bf16_t* X, bool first) {
+  GemmDesc g = apply_desc(j, X, j.fuse_W, first);
+  g.ldd = j.p.n; g.strideD = j.p.m * j.p.n;
+  g.C = j.fuse_W; g.ldc = g.ldd; g.strideC = g.strideD;
+  g.alpha = -j.fuse_step; g.beta = j.fuse_decay;
+  return g;
+}
 
 // The `iters` Newton-Schulz iterations on n independent jobs.  On return result_buf of a job
 // is the index of the buffer that holds its result; with iters == 0 the result is X[0] still
@@ -223,18 +242,23 @@ int run_ns_jobs(NsJob* jobs, int n, int iters, float a, float b, float c, float 
     for (int i = 0; i < nbig; ++i) d[i] = poly_desc(*big[i], a, b, c);
     rc = launch_ns_gemm_set(d, nbig, stream);
     if (rc != MLC_OK) return rc;
-    for (int i = 0; i < nbig; ++i) d[i] = apply_desc(*big[i], big[i]->w.X[cur], big[i]->w.X[cur ^ 1], it == 0);
+    const bool last = it + 1 == iters;
+    for (int i = 0; i < nbig; ++i)
+      d[i] = (last && big[i]->fuse_W) ? apply_update_desc(*big[i], big[i]->w.X[cur], it == 0)
+                                      : apply_desc(*big[i], big[i]->w.X[cur], big[i]->w.X[cur ^ 1], it == 0);
     rc = launch_ns_gemm_set(d, nbig, stream);
     if (rc != MLC_OK) return rc;
     cur ^= 1;
   }
-  for (int i = 0; i < nbig; ++i) big[i]->result_buf = cur;
+  for (int i = 0; i < nbig; ++i) big[i]->result_buf = (iters >= 1 && big[i]->fuse_W) ? -1 : cur;
   return MLC_OK;
 }
 
 int run_ns_chunk(const NsPlan& p, const NsBuffers& w, int64_t chunk, int iters, float a, float b,
-                 float c, float eps, hipStream_t stream, int* result_buf) {
+                 float c, float eps, hipStream_t stream, int* result_buf, bf16_t* fuse_W = nullptr,
+                 float fuse_decay = 0.f, float fuse_step = 0.f) {
   NsJob j{p, w, chunk, 0};
+  j.fuse_W = fuse_W; j.fuse_decay = fuse_decay; j.fuse_step = fuse_step;
   const int rc = run_ns_jobs(&j, 1, iters, a, b, c, eps, stream);
   *result_buf = j.result_buf;
   return rc;
@@ -431,6 +455,11 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
       jobs[gi].chunk = g.count;
       jobs[gi].w = carve(jobs[gi].p, base, g.count);
       jobs[gi].result_buf = 0;
+      if (can_fuse_update(jobs[gi].p, g.param_dtype, hp->ns_iters)) {
+        jobs[gi].fuse_W = (bf16_t*)g.param;
+        jobs[gi].fuse_decay = decay_factor;
+        jobs[gi].fuse_step = hp->eta * g.lr_scale;
+      }
       base += jobs[gi].p.per_matrix * (size_t)g.count;
       rc = launch_momentum(g.grad, g.grad_dtype, g.momentum, jobs[gi].w.X[0], jobs[gi].w.partials,
                            jobs[gi].p.nblk, g.count, g.m, g.n, jobs[gi].p.mp, jobs[gi].p.np, jobs[gi].p.ldx,
@@ -442,6 +471,7 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
     for (int gi = 0; gi < n_groups; ++gi) {
       const mlc_inner_group& g = groups[gi];
       const NsJob& j = jobs[gi];
+      if (j.result_buf < 0) continue;      // the last product wrote W
       rc = launch_param_update(g.param, g.param_dtype, j.w.X[j.result_buf],
                                hp->ns_iters == 0 ? j.w.scale : nullptr, g.count, g.m, g.n, j.p.mp, j.p.ldx,
                                decay_factor, hp->eta * g.lr_scale, stream);
@@ -464,8 +494,11 @@ int muloco_inner_step(const mlc_inner_group* groups, int n_groups, const mlc_muo
                            p.np, p.ldx, hp->beta, hp->nesterov, stream);
       if (rc != MLC_OK) return rc;
       int res = 0;
-      rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, hp->ns_eps, stream, &res);
+      const bool fuse = can_fuse_update(p, g.param_dtype, hp->ns_iters);
+      rc = run_ns_chunk(p, w, cc, hp->ns_iters, hp->ns_a, hp->ns_b, hp->ns_c, hp->ns_eps, stream, &res,
+                        fuse ? (bf16_t*)param : nullptr, decay_factor, hp->eta * g.lr_scale);
       if (rc != MLC_OK) return rc;
+      if (res < 0) continue;               // the last product wrote W
       rc = launch_param_update(param, g.param_dtype, w.X[res], hp->ns_iters == 0 ? w.scale : nullptr,
                                cc, g.m, g.n, p.mp, p.ldx, decay_factor, hp->eta * g.lr_scale, stream);
       if (rc != MLC_OK) return rc;

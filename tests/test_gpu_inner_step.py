@@ -61,6 +61,10 @@ CASES = [
     (2, 200, 136, torch.bfloat16, torch.float32),
     (1, 333, 77, torch.float32, torch.bfloat16),
     (2, 768, 768, torch.bfloat16, torch.bfloat16),
+    # bf16 weights of a shape the products work on unpadded: the last product writes the update
+    (2, 768, 3072, torch.bfloat16, torch.bfloat16),
+    (2, 3072, 768, torch.bfloat16, torch.float32),
+    (70, 256, 512, torch.bfloat16, torch.bfloat16),    # enough tiles for the 256 x 256 tile
 ]
 
 
@@ -93,6 +97,23 @@ def test_several_groups_one_call_and_small_work_space():
     torch.cuda.synchronize()
     for (W0, g, m0), grp, (c, m, n) in zip(host, dev, shapes):
         _check_group(W0, g, m0, grp.param.cpu(), grp.momentum.cpu(), hp, math.sqrt(n / m), f"group {m}x{n}")
+
+
+def test_zero_gradient_decays_bf16_weights_through_the_last_product():
+    hp = mlc.MuonHParams(eta=0.1, weight_decay=0.05, beta=0.9)
+    W0 = S.normal((2, 256, 640), S.PARAM_STD, 0, 8, dtype=torch.bfloat16)
+    W = W0.to(DEV)
+    g = torch.zeros_like(W)
+    mom = torch.zeros((2, 256, 640), dtype=torch.float32, device=DEV)
+    grp = mlc.InnerGroup(W, g, mom, 1.0)
+    ws = torch.empty(mlc.muloco_inner_workspace_bytes([grp]), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step([grp], hp, ws)
+    torch.cuda.synchronize()
+    ref = storage.round_to_storage(to_f64(W0) * np.float64(np.float32(1) - np.float32(0.1) * np.float32(0.05)), "bf16")
+    got = to_f64(W.cpu())
+    # one bf16 rounding of decay * W: equal up to the fp32 product's own rounding before it
+    assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)) <= 2.0 ** -7
+    assert np.mean(got != ref) < 1e-3
 
 
 def test_zero_gradient_and_momentum_only_decays():
