@@ -93,6 +93,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="1.76b", help="tiny | 150m | 1.76b | 3.1b | 15b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the legs on the 150M- and 3.1B-scale workloads (profiles of one workload's kernels)")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--workspace-gb", type=float, default=None)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -374,9 +376,10 @@ def main() -> int:
         torch.cuda.empty_cache()
         return fig
 
-    ns_150m = inner_on("150m", 10) if wl.name != "150m" else None
-    outer_k8_150m = outer_on("150m", 0, 10)
-    quantised_outer_k4_31b = outer_on("3.1b", 4, 3)
+    others = not args.no_other_workloads
+    ns_150m = inner_on("150m", 10) if others and wl.name != "150m" else None
+    outer_k8_150m = outer_on("150m", 0, 10) if others else None
+    quantised_outer_k4_31b = outer_on("3.1b", 4, 3) if others else None
 
     ms_per_step = wall * 1e3 / args.steps
     gemm = timing["ns_gemm"]
