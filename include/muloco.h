@@ -110,6 +110,9 @@ int newton_schulz_static_scratch(const void* in, void* out, int io_dtype,
  *     O    = newton_schulz(U)          (as above)
  *     W   <- W - eta * lr_scale * O - eta * weight_decay * W
  * The paper asks for lr_scale = sqrt(n/m) for an m x n matrix; the caller supplies it.
+ * For bf16 W with m and n multiples of 128 (and matrices larger than 128 x 512) the last line
+ * is the epilogue of the last Newton-Schulz product: O is then used unrounded (fp32) and never
+ * stored; otherwise O is rounded to bf16 and a separate pass applies it.
  */
 typedef struct {
   int64_t count, m, n;
