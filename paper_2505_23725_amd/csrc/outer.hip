@@ -14,56 +14,6 @@ namespace {
 
 constexpr int OT_THREADS = 256;
 
-template <typename T> struct Ld;
-template <> struct Ld<float> {
-  static __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  }
-  static __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
-    f32x4 a, b;
-    a.x = v[0]; a.y = v[1]; a.z = v[2]; a.w = v[3]; b.x = v[4]; b.y = v[5]; b.z = v[6]; b.w = v[7];
-    *reinterpret_cast<f32x4*>(p) = a;
-    *reinterpret_cast<f32x4*>(p + 4) = b;
-  }
-  static __device__ __forceinline__ float load1(const float* p) { return *p; }
-  static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
-  static __device__ __forceinline__ float round(float v) { return v; }   // value as stored
-  // 8 values as they sit in memory (held back while earlier values are worked on)
-  struct raw_t { f32x4 a, b; };
-  static __device__ __forceinline__ raw_t load_raw(const float* p) {
-    raw_t r;
-    r.a = *reinterpret_cast<const f32x4*>(p);
-    r.b = *reinterpret_cast<const f32x4*>(p + 4);
-    return r;
-  }
-  static __device__ __forceinline__ void unpack(const raw_t& r, float (&v)[8]) {
-    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
-  }
-};
-template <> struct Ld<bf16_t> {
-  static __device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
-    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
-    v[0] = bf16lo(w.x); v[1] = bf16hi(w.x); v[2] = bf16lo(w.y); v[3] = bf16hi(w.y);
-    v[4] = bf16lo(w.z); v[5] = bf16hi(w.z); v[6] = bf16lo(w.w); v[7] = bf16hi(w.w);
-  }
-  static __device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
-    u32x4 w;
-    w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
-    w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
-    *reinterpret_cast<u32x4*>(p) = w;
-  }
-  static __device__ __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(*p); }
-  static __device__ __forceinline__ void store1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
-  static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
-  typedef u32x4 raw_t;
-  static __device__ __forceinline__ raw_t load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
-  static __device__ __forceinline__ void unpack(const raw_t& w, float (&v)[8]) {
-    v[0] = bf16lo(w.x); v[1] = bf16hi(w.x); v[2] = bf16lo(w.y); v[3] = bf16hi(w.y);
-    v[4] = bf16lo(w.z); v[5] = bf16hi(w.z); v[6] = bf16lo(w.w); v[7] = bf16hi(w.w);
-  }
-};
-
 // eq. 3; theta comes back as the value the global buffer will hold after the store, so the
 // write-back hands every worker exactly the new theta_g.
 template <typename GT>
@@ -71,7 +21,7 @@ __device__ __forceinline__ void outer_update(float& theta, float& u, float psi, 
                                              int nesterov) {
   const float step = eta * psi;
   u = mu * u + step;
-  theta = Ld<GT>::round(nesterov ? theta - mu * u - step : theta - u);
+  theta = Vec8<GT>::round(nesterov ? theta - mu * u - step : theta - u);
 }
 
 // ---- unquantised fused outer step ---------------------------------------------------
@@ -84,34 +34,34 @@ __device__ __forceinline__ void outer_fused_body(
   for (long i = blk * OT_THREADS + threadIdx.x; i < n_vec; i += nblk * OT_THREADS) {
     const long off = i * 8;
     float tg[8], uv[8], acc[8];
-    Ld<GT>::load8(theta_g + off, tg);
-    Ld<float>::load8(u + off, uv);
+    Vec8<GT>::load(theta_g + off, tg);
+    Vec8<float>::load(u + off, uv);
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int k = 0; k < K; ++k) {
       float tk[8];
-      Ld<WT>::load8(reinterpret_cast<const WT*>(w.p[k]) + off, tk);
+      Vec8<WT>::load(reinterpret_cast<const WT*>(w.p[k]) + off, tk);
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] += tg[j] - tk[j];
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) outer_update<GT>(tg[j], uv[j], acc[j] * inv_k, eta, mu, nesterov);
-    Ld<GT>::store8(theta_g + off, tg);
-    Ld<float>::store8(u + off, uv);
+    Vec8<GT>::store(theta_g + off, tg);
+    Vec8<float>::store(u + off, uv);
     if (write_back)
-      for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + off, tg);
+      for (int k = 0; k < K; ++k) Vec8<WT>::store(reinterpret_cast<WT*>(w.p[k]) + off, tg);
   }
   // ragged tail (fewer than 8 elements), one thread each
   const long tail0 = n_vec * 8;
   const long t = tail0 + blk * OT_THREADS + threadIdx.x;
   if (t < n_elems) {
-    float tg = Ld<GT>::load1(theta_g + t), uv = u[t], acc = 0.f;
-    for (int k = 0; k < K; ++k) acc += tg - Ld<WT>::load1(reinterpret_cast<const WT*>(w.p[k]) + t);
+    float tg = Vec8<GT>::load1(theta_g + t), uv = u[t], acc = 0.f;
+    for (int k = 0; k < K; ++k) acc += tg - Vec8<WT>::load1(reinterpret_cast<const WT*>(w.p[k]) + t);
     outer_update<GT>(tg, uv, acc * inv_k, eta, mu, nesterov);
-    Ld<GT>::store1(theta_g + t, tg);
+    Vec8<GT>::store1(theta_g + t, tg);
     u[t] = uv;
     if (write_back)
-      for (int k = 0; k < K; ++k) Ld<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + t, tg);
+      for (int k = 0; k < K; ++k) Vec8<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + t, tg);
   }
 }
 
@@ -245,10 +195,10 @@ __global__ __launch_bounds__(OT_THREADS) void matrix_range_kernel(
        i += (long)gridDim.x * OT_THREADS * W) {
     float a[8], c[8], e[8];
     if (VEC) {
-      Ld<GT>::load8(tg + i, a); Ld<WT>::load8(tk + i, c);
-      if (res) Ld<float>::load8(res + i, e);
+      Vec8<GT>::load(tg + i, a); Vec8<WT>::load(tk + i, c);
+      if (res) Vec8<float>::load(res + i, e);
     } else {
-      a[0] = Ld<GT>::load1(tg + i); c[0] = Ld<WT>::load1(tk + i);
+      a[0] = Vec8<GT>::load1(tg + i); c[0] = Vec8<WT>::load1(tk + i);
       if (res) e[0] = res[i];
     }
 #pragma unroll
@@ -315,11 +265,11 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
       for (int c = lane * W; c < n; c += 64 * W) {
         float a[8], b[8], e[8];
         if (VEC) {
-          Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
-          if (res) Ld<float>::load8(res + c, e);
+          Vec8<GT>::load(tg + c, a); Vec8<WT>::load(tk + c, b);
+          if (res) Vec8<float>::load(res + c, e);
         } else {
           for (int j = 0; j < W; ++j) {
-            a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
+            a[j] = Vec8<GT>::load1(tg + c + j); b[j] = Vec8<WT>::load1(tk + c + j);
             if (res) e[j] = res[c + j];
           }
         }
@@ -339,11 +289,11 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
     for (int c = lane * W; c < n; c += 64 * W) {
       float a[8], b[8], e[8];
       if (VEC) {
-        Ld<GT>::load8(tg + c, a); Ld<WT>::load8(tk + c, b);
-        if (res) Ld<float>::load8(res + c, e);
+        Vec8<GT>::load(tg + c, a); Vec8<WT>::load(tk + c, b);
+        if (res) Vec8<float>::load(res + c, e);
       } else {
         for (int j = 0; j < W; ++j) {
-          a[j] = Ld<GT>::load1(tg + c + j); b[j] = Ld<WT>::load1(tk + c + j);
+          a[j] = Vec8<GT>::load1(tg + c + j); b[j] = Vec8<WT>::load1(tk + c + j);
           if (res) e[j] = res[c + j];
         }
       }
@@ -356,7 +306,7 @@ __global__ __launch_bounds__(OT_THREADS) void quantize_rows_kernel(
       }
       if (VEC) {
         store_codes8(crow, c, q, bits, form.code_bias);
-        if (res) Ld<float>::store8(res + c, e);
+        if (res) Vec8<float>::store(res + c, e);
       } else {
         unsigned int p = 0;
         for (int j = 0; j < W; ++j) p |= (unsigned int)(q[j] + form.code_bias) << (bits * j);
@@ -398,7 +348,7 @@ __device__ __forceinline__ void quantize_rows_reg_body(
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (t + i * G) * 8;
-    if (live && c < n) Ld<GT>::load8(theta_g + rbase + c, tg[i]);
+    if (live && c < n) Vec8<GT>::load(theta_g + rbase + c, tg[i]);
     else
 #pragma unroll
       for (int j = 0; j < 8; ++j) tg[i][j] = 0.f;
@@ -408,14 +358,14 @@ __device__ __forceinline__ void quantize_rows_reg_body(
   }
   // The next worker's row is requested before this worker's row is reduced and quantised, so
   // that with several workers only the first request waits for memory with nothing to do.
-  typedef typename Ld<WT>::raw_t RawT;
+  typedef typename Vec8<WT>::raw_t RawT;
   RawT ahead[NV];
   auto request = [&](int k) {
     const WT* tk = reinterpret_cast<const WT*>(w.p[k]) + rbase;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = (t + i * G) * 8;
-      if (live && c < n) ahead[i] = Ld<WT>::load_raw(tk + c);
+      if (live && c < n) ahead[i] = Vec8<WT>::load_raw(tk + c);
     }
   };
   request(0);
@@ -432,12 +382,12 @@ __device__ __forceinline__ void quantize_rows_reg_body(
       const int c = (t + i * G) * 8;
       if (live && c < n) {
         float b[8];
-        Ld<WT>::unpack(cur[i], b);
+        Vec8<WT>::unpack(cur[i], b);
 #pragma unroll
         for (int j = 0; j < 8; ++j) d[i][j] = tg[i][j] - b[j];
         if (res) {
           float e[8];
-          Ld<float>::load8(res + c, e);
+          Vec8<float>::load(res + c, e);
 #pragma unroll
           for (int j = 0; j < 8; ++j) d[i][j] = ef_input(d[i][j], e[j], form.ef_beta);
         }
@@ -480,7 +430,7 @@ __device__ __forceinline__ void quantize_rows_reg_body(
           if constexpr (OUTER) acc[i][j] += sent;
         }
         store_codes8(crow, c, q, bits, form.code_bias);
-        if (res) Ld<float>::store8(res + c, e);
+        if (res) Vec8<float>::store(res + c, e);
       }
     }
   }
@@ -531,13 +481,13 @@ __device__ __forceinline__ void quantize_rows_reg_body(
       const int c = (t + i * G) * 8;
       if (live && c < n) {
         float uv[8];
-        Ld<float>::load8(u + rbase + c, uv);
+        Vec8<float>::load(u + rbase + c, uv);
 #pragma unroll
         for (int j = 0; j < 8; ++j) outer_update<GT>(tg[i][j], uv[j], acc[i][j], eta, mu, nesterov);
-        Ld<GT>::store8(theta_g + rbase + c, tg[i]);
-        Ld<float>::store8(u + rbase + c, uv);
+        Vec8<GT>::store(theta_g + rbase + c, tg[i]);
+        Vec8<float>::store(u + rbase + c, uv);
         if (write_back)
-          for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + rbase + c, tg[i]);
+          for (int k = 0; k < K; ++k) Vec8<WT>::store(reinterpret_cast<WT*>(w.p[k]) + rbase + c, tg[i]);
       }
     }
   }
@@ -643,9 +593,9 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     const long off = row * n + c;
     const long grp = form.rows_per_range ? row / form.rows_per_range : row;
     float tg[8], uv[8], acc[8];
-    if (VEC) { Ld<GT>::load8(theta_g + off, tg); Ld<float>::load8(u + off, uv); }
+    if (VEC) { Vec8<GT>::load(theta_g + off, tg); Vec8<float>::load(u + off, uv); }
     else
-      for (int j = 0; j < W; ++j) { tg[j] = Ld<GT>::load1(theta_g + off + j); uv[j] = u[off + j]; }
+      for (int j = 0; j < W; ++j) { tg[j] = Vec8<GT>::load1(theta_g + off + j); uv[j] = u[off + j]; }
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     for (int k = 0; k < K; ++k) {
@@ -662,16 +612,16 @@ __global__ __launch_bounds__(OT_THREADS) void dequant_outer_kernel(
     }
     for (int j = 0; j < W; ++j) outer_update<GT>(tg[j], uv[j], __fmul_rn(acc[j], inv_k), eta, mu, nesterov);
     if (VEC) {
-      Ld<GT>::store8(theta_g + off, tg);
-      Ld<float>::store8(u + off, uv);
+      Vec8<GT>::store(theta_g + off, tg);
+      Vec8<float>::store(u + off, uv);
       if (write_back)
-        for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + off, tg);
+        for (int k = 0; k < K; ++k) Vec8<WT>::store(reinterpret_cast<WT*>(w.p[k]) + off, tg);
     } else {
       for (int j = 0; j < W; ++j) {
-        Ld<GT>::store1(theta_g + off + j, tg[j]);
+        Vec8<GT>::store1(theta_g + off + j, tg[j]);
         u[off + j] = uv[j];
         if (write_back)
-          for (int k = 0; k < K; ++k) Ld<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + off + j, tg[j]);
+          for (int k = 0; k < K; ++k) Vec8<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + off + j, tg[j]);
       }
     }
   }
@@ -713,10 +663,10 @@ __global__ __launch_bounds__(OT_THREADS) void topk_hist_kernel(
        i += (long)gridDim.x * OT_THREADS * W) {
     float a[8], c[8], e[8];
     if (VEC) {
-      Ld<GT>::load8(tg + i, a); Ld<WT>::load8(tk + i, c);
-      if (res) Ld<float>::load8(res + i, e);
+      Vec8<GT>::load(tg + i, a); Vec8<WT>::load(tk + i, c);
+      if (res) Vec8<float>::load(res + i, e);
     } else {
-      a[0] = Ld<GT>::load1(tg + i); c[0] = Ld<WT>::load1(tk + i);
+      a[0] = Vec8<GT>::load1(tg + i); c[0] = Vec8<WT>::load1(tk + i);
       if (res) e[0] = res[i];
     }
 #pragma unroll
@@ -816,8 +766,8 @@ __global__ __launch_bounds__(OT_THREADS) void topk_outer_kernel(
   for (long i = ((long)blockIdx.x * OT_THREADS + threadIdx.x) * W; i < elems;
        i += (long)gridDim.x * OT_THREADS * W) {
     float a[8], uv[8], acc[8];
-    if (VEC) { Ld<GT>::load8(tg + i, a); Ld<float>::load8(ub + i, uv); }
-    else { a[0] = Ld<GT>::load1(tg + i); uv[0] = ub[i]; }
+    if (VEC) { Vec8<GT>::load(tg + i, a); Vec8<float>::load(ub + i, uv); }
+    else { a[0] = Vec8<GT>::load1(tg + i); uv[0] = ub[i]; }
 #pragma unroll
     for (int j = 0; j < W; ++j) acc[j] = 0.f;
     for (int k = 0; k < K; ++k) {
@@ -825,10 +775,10 @@ __global__ __launch_bounds__(OT_THREADS) void topk_outer_kernel(
       float* res = ef.p[k] ? ef.p[k] + b * elems : nullptr;
       float c[8], e[8];
       if (VEC) {
-        Ld<WT>::load8(tk + i, c);
-        if (res) Ld<float>::load8(res + i, e);
+        Vec8<WT>::load(tk + i, c);
+        if (res) Vec8<float>::load(res + i, e);
       } else {
-        c[0] = Ld<WT>::load1(tk + i);
+        c[0] = Vec8<WT>::load1(tk + i);
         if (res) e[0] = res[i];
       }
 #pragma unroll
@@ -840,22 +790,22 @@ __global__ __launch_bounds__(OT_THREADS) void topk_outer_kernel(
         e[j] = keep ? 0.f : v;           // what was not sent
       }
       if (res) {
-        if (VEC) Ld<float>::store8(res + i, e);
+        if (VEC) Vec8<float>::store(res + i, e);
         else res[i] = e[0];
       }
     }
 #pragma unroll
     for (int j = 0; j < W; ++j) outer_update<GT>(a[j], uv[j], __fmul_rn(acc[j], inv_k), eta, mu, nesterov);
     if (VEC) {
-      Ld<GT>::store8(tg + i, a);
-      Ld<float>::store8(ub + i, uv);
+      Vec8<GT>::store(tg + i, a);
+      Vec8<float>::store(ub + i, uv);
       if (write_back)
-        for (int k = 0; k < K; ++k) Ld<WT>::store8(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a);
+        for (int k = 0; k < K; ++k) Vec8<WT>::store(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a);
     } else {
-      Ld<GT>::store1(tg + i, a[0]);
+      Vec8<GT>::store1(tg + i, a[0]);
       ub[i] = uv[0];
       if (write_back)
-        for (int k = 0; k < K; ++k) Ld<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a[0]);
+        for (int k = 0; k < K; ++k) Vec8<WT>::store1(reinterpret_cast<WT*>(w.p[k]) + b * elems + i, a[0]);
     }
   }
 }
