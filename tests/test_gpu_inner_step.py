@@ -182,3 +182,37 @@ def test_groups_side_by_side_give_the_bits_of_one_group_after_the_other(shapes):
         sl = slice(c - 1, c)        # the last matrix of every group
         _check_group(W0[sl], g[sl], m0[sl], grp.param[sl].cpu(), grp.momentum[sl].cpu(), hp, math.sqrt(n / m),
                      f"group {m}x{n}")
+
+
+def test_groups_of_different_kinds_side_by_side():
+    """One call over groups that take different routes: bf16 weights of an unpadded shape (the
+    last product writes the update), fp32 weights (separate update pass), a ragged bf16 shape
+    (padded work space, separate pass) and small matrices (one-launch chain).  Same bits as one
+    group per call with the small work space, and every group against the oracle."""
+    hp = mlc.MuonHParams(eta=0.05, weight_decay=0.01, beta=0.9)
+    kinds = [(40, 256, 512, torch.bfloat16), (40, 512, 256, torch.float32), (3, 200, 520, torch.bfloat16),
+             (5, 128, 256, torch.bfloat16)]
+
+    def build():
+        out = []
+        for i, (c, m, n, pd) in enumerate(kinds):
+            W0, g, m0 = _make_group(c, m, n, pd, torch.bfloat16, seed=70 + i)
+            out.append((W0, g, m0, mlc.InnerGroup(W0.to(DEV), g.to(DEV), m0.to(DEV), math.sqrt(n / m))))
+        return out
+
+    both, alone = build(), build()
+    groups = [t[3] for t in both]
+    ws = torch.empty(mlc.muloco_inner_workspace_bytes(groups), dtype=torch.uint8, device=DEV)
+    mlc.muloco_inner_step(groups, hp, ws)
+    for t in alone:
+        small = torch.empty(mlc.muloco_inner_workspace_min_bytes([t[3]]), dtype=torch.uint8, device=DEV)
+        mlc.muloco_inner_step([t[3]], hp, small)
+    torch.cuda.synchronize()
+    for a, b, (c, m, n, pd) in zip(both, alone, kinds):
+        bits = torch.int16 if pd == torch.bfloat16 else torch.int32
+        assert torch.equal(a[3].param.view(bits), b[3].param.view(bits)), f"{m}x{n}: weights differ"
+        assert torch.equal(a[3].momentum.view(torch.int32), b[3].momentum.view(torch.int32))
+    for (W0, g, m0, grp), (c, m, n, pd) in zip(both, kinds):
+        sl = slice(c - 2, c)
+        _check_group(W0[sl], g[sl], m0[sl], grp.param[sl].cpu(), grp.momentum[sl].cpu(), hp, math.sqrt(n / m),
+                     f"group {m}x{n} {dtype_name(W0)}")
