@@ -493,8 +493,15 @@ __device__ __forceinline__ void quantize_rows_reg_body(
   }
 }
 
+// Wavefronts per SIMD the register allocation is held to: one more than the compiler reaches on
+// its own where that is a few registers away (these kernels wait on memory with little else to
+// do, so a resident wavefront more is worth more than the registers).
+constexpr int quant_min_waves(int nv, bool outer) {
+  return outer ? (nv <= 1 ? 6 : nv <= 2 ? 4 : nv <= 4 ? 3 : 1) : (nv <= 1 ? 7 : nv <= 2 ? 5 : nv <= 4 ? 3 : 1);
+}
+
 template <typename WT, typename GT, int NV, int G, bool OUTER>
-__global__ __launch_bounds__(OT_THREADS) void quantize_rows_reg_kernel(
+__global__ __launch_bounds__(OT_THREADS, quant_min_waves(NV, OUTER)) void quantize_rows_reg_kernel(
     WorkerPtrs w, GT* __restrict__ theta_g, float* __restrict__ u, CodePtrs codes, ScalePtrs scales,
     OffsetPtrs offsets, ResidualPtrs ef, long rows, int n, int K, QuantForm form, float eta, float mu,
     float inv_k, int nesterov, int write_back, int requant, uint8_t* mean_codes, float* mean_scales,
@@ -532,7 +539,7 @@ __host__ __device__ constexpr RegCfg reg_cfg(int idx) {
 }
 
 template <typename WT, typename GT>
-__global__ __launch_bounds__(OT_THREADS) void quantize_outer_multi_kernel(
+__global__ __launch_bounds__(OT_THREADS, 3) void quantize_outer_multi_kernel(
     QuantSegTable tab, int K, QuantForm form, float eta, float mu, float inv_k, int nesterov, int write_back) {
   int si = 0;
 #pragma unroll
