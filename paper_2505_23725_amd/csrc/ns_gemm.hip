@@ -45,7 +45,7 @@ namespace {
 
 constexpr int BK = 32;           // K depth of one LDS stage
 constexpr int NSTAGE = 5;        // stages in the LDS ring
-constexpr int NPRE = 4;          // K tiles requested when an output tile starts
+constexpr int NPRE = 4;          // K tiles of an output tile that are requested ahead of its first step
 constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;        // most tile rows per group of the tile order
