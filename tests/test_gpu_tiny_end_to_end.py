@@ -56,13 +56,18 @@ def test_tiny_workload_h8_then_outer_step():
     print(f"tiny workload: worst displacement error after H={wl.H} steps {worst:.3e}")
 
 
-def test_graph_replay_equals_eager_steps():
+# bf16 weights and matrices large enough for the batched GEMM kernels (shared launches, the
+# update written by the last product), small enough to run in a moment
+MID = S.Workload("mid", 40, 256, 1024, K=1, H=4, param_dtype="bf16")
+
+
+@pytest.mark.parametrize("wl", [S.WORKLOADS["tiny"], MID], ids=["tiny", "mid-bf16"])
+def test_graph_replay_equals_eager_steps(wl):
     """The whole step (Muon inner step, outer step, 4-bit quantised outer step per layer) is
     captured into a HIP graph once; replays, with eager work and synchronisations between
     them, must give the bits that the same number of eager steps gives."""
     import paper_2505_23725_amd as mlc
     from paper_2505_23725_amd.harness import MulocoJob
-    wl = S.WORKLOADS["tiny"]
 
     def make():
         job = MulocoJob(wl, generate_on="cpu", seed=3, K=2, with_quant=True)
